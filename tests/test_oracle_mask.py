@@ -1,0 +1,153 @@
+"""Pins for the oracle's Algorithm 2 (MeanPooling block selection) and its forced blocks.  CPU only."""
+import itertools
+import math
+import os
+
+import numpy as np
+import pytest
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rows_from_probs(p, d):
+    """Build Q' (one block-constant query) and K' blocks whose pooled logits give softmax == p exactly-ish:
+    Qbar = e0, Kbar_j = ln(p_j) * e0 with scale 1."""
+    T = len(p)
+    Kp = np.zeros((1, 1, T, d), dtype=np.float32)
+    Kp[0, 0, :, 0] = np.log(np.asarray(p, dtype=np.float64)).astype(np.float32)
+    Qp = np.zeros((1, 1, T, d), dtype=np.float32)
+    Qp[0, 0, :, 0] = 1.0
+    return Qp, Kp
+
+
+def test_hand_worked_row(oracle):
+    # block size 1 so block means are the tokens; no permutation (segment > N); scale 1.
+    # Row 5 sees p = [.38, .1, .2, .1, .2, .02].  Sorted with ties by lowest index:
+    #   order 0(.38) 2(.2) 4(.2) 1(.1) 3(.1) 5(.02), cumulative .38 .58 .78 .88 .98 1.
+    # The diagonal block (5) is always forced on top of the first k of that order.
+    p = [0.38, 0.1, 0.2, 0.1, 0.2, 0.02]
+    Qp, Kp = _rows_from_probs(p, d=4)
+    cases = [(0.30, 1, [0, 5]), (0.50, 2, [0, 2, 5]), (0.70, 3, [0, 2, 4, 5]), (0.85, 4, [0, 1, 2, 4, 5]),
+             (0.95, 5, [0, 1, 2, 3, 4, 5]), (0.99, 6, [0, 1, 2, 3, 4, 5]), (1.50, 6, [0, 1, 2, 3, 4, 5]),
+             (0.0, 1, [0, 5]), (-1.0, 1, [0, 5])]
+    for tau, want_k, want_cols in cases:
+        mask, cnt, cols, probs, k = oracle.block_mask(Qp, Kp, block=1, segment=8, tau=tau, scale=1.0, flags=0,
+                                                      want_probs=True)
+        np.testing.assert_allclose(probs[0, 0, 5], p, rtol=1e-6)
+        assert k[0, 0, 5] == want_k, tau
+        assert cols[0, 0, 5, :cnt[0, 0, 5]].tolist() == want_cols, tau
+        assert mask[0, 0, 5].tolist() == [int(j in want_cols) for j in range(6)]
+
+
+def test_uniform_rows_closed_form(oracle):
+    # all-zero queries -> every allowed block has probability 1/n -> k = ceil(tau*n) (n a power of two, tau dyadic:
+    # every partial sum is exact)
+    T, d = 16, 8
+    Qp = np.zeros((1, 1, T, d), dtype=np.float32)
+    Kp = np.random.default_rng(0).standard_normal((1, 1, T, d)).astype(np.float32)
+    mask, cnt, cols, probs, k = oracle.block_mask(Qp, Kp, 1, T + 1, 0.75, 1.0, 0, want_probs=True)
+    for i in [0, 1, 3, 7, 15]:
+        n = i + 1
+        assert k[0, 0, i] == math.ceil(0.75 * n)
+        want = set(range(math.ceil(0.75 * n))) | {i}          # lowest indices first on ties, plus the diagonal
+        assert set(cols[0, 0, i, :cnt[0, 0, i]].tolist()) == want
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_k_is_minimum_cardinality_by_brute_force(oracle, seed):
+    # Among all subsets of the allowed blocks, the smallest one whose pooled mass reaches tau has exactly k
+    # elements, and the oracle's pick is the heaviest subset of that size.
+    rng = np.random.default_rng(seed)
+    T, d, block = 10, 8, 4
+    N = T * block
+    Qp = (2.0 * rng.standard_normal((1, 2, N, d))).astype(np.float32)
+    Kp = (2.0 * rng.standard_normal((1, 1, N, d))).astype(np.float32)
+    tau = 0.8
+    mask, cnt, cols, probs, k = oracle.block_mask(Qp, Kp, block, N + block, tau, 0.0, 0, want_probs=True)
+    for h in range(2):
+        for i in range(T):
+            a = probs[0, h, i, :i + 1]
+            best = None
+            for size in range(1, i + 2):
+                masses = [(sum(a[list(c)]), c) for c in itertools.combinations(range(i + 1), size)]
+                top = max(masses)
+                if top[0] >= tau or size == i + 1:
+                    best = (size, set(top[1]))
+                    break
+            assert k[0, h, i] == best[0]
+            sel = set(np.flatnonzero(mask[0, h, i]).tolist())
+            assert sel == best[1] | {i}
+            # kept pooled mass reaches tau unless everything allowed was kept
+            assert a[sorted(sel)].sum() >= tau - 1e-12 or len(sel) == i + 1
+
+
+def test_pooling_uses_valid_rows_of_partial_last_block(oracle):
+    # N = 5, block 4: the last block has one row; its mean is that row, not row/4.
+    d = 2
+    Qp = np.zeros((1, 1, 5, d), dtype=np.float32)
+    Qp[0, 0, 4, 0] = 1.0
+    Kp = np.zeros((1, 1, 5, d), dtype=np.float32)
+    Kp[0, 0, 0:4, 0] = np.float32(math.log(3.0))      # block 0 mean = ln3
+    Kp[0, 0, 4, 0] = 0.0                              # block 1 mean = 0
+    mask, cnt, cols, probs, k = oracle.block_mask(Qp, Kp, 4, 8, 0.5, 1.0, 0, want_probs=True)
+    np.testing.assert_allclose(probs[0, 0, 1, :2], [0.75, 0.25], rtol=1e-6)
+
+
+def test_allowed_region_and_forced_blocks_under_segments(oracle):
+    # block 2, segment 8 (R=4), N = 21 -> T=11, G=2 full segments (blocks 0-3, 4-7), tail blocks 8,9,10.
+    rng = np.random.default_rng(4)
+    N, d = 21, 4
+    Qp = rng.standard_normal((1, 1, N, d)).astype(np.float32)
+    Kp = rng.standard_normal((1, 1, N, d)).astype(np.float32)
+    mask, cnt, cols, probs, k = oracle.block_mask(Qp, Kp, 2, 8, 0.0, 0.0, 0, want_probs=True)
+    T, R, G = 11, 4, 2
+    for i in range(T):
+        g = i // R
+        n_i = (g + 1) * R if g < G else i + 1
+        assert (probs[0, 0, i, :n_i] > 0).all() and (probs[0, 0, i, n_i:] == 0).all()
+        np.testing.assert_allclose(probs[0, 0, i].sum(), 1.0, rtol=1e-13)
+        forced = set(range(g * R, n_i)) if g < G else {i}
+        sel = set(np.flatnonzero(mask[0, 0, i]).tolist())
+        assert forced <= sel and len(sel - forced) <= 1            # tau = 0 -> k = 1
+        assert k[0, 0, i] == 1
+    # flag bit 0 adds the first block everywhere
+    m1, c1, _ = oracle.block_mask(Qp, Kp, 2, 8, 0.0, 0.0, 1)
+    assert (m1[0, 0, :, 0] == 1).all()
+    assert ((m1 == 1) >= (mask == 1)).all()
+
+
+def test_tau_one_selects_everything_allowed_and_counts_match_table5(oracle):
+    # With no permutation (segment > N) and tau >= 1 every causal block is selected; the totals must be the
+    # "total causal blocks" column the paper prints for block size 128.
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "table5_causal_block_totals.txt")) if l[0] != "#"]
+    d = 2
+    for n_str, total_str in rows:
+        N, total = int(n_str), int(total_str)
+        if N > 32768:
+            # the closed form the paper states, for the sizes too slow to run through the oracle here
+            T = -(-N // 128)
+            assert T * (T + 1) // 2 == total
+            continue
+        rng = np.random.default_rng(N)
+        Qp = rng.standard_normal((1, 1, N, d)).astype(np.float32)
+        Kp = rng.standard_normal((1, 1, N, d)).astype(np.float32)
+        mask, cnt, cols = oracle.block_mask(Qp, Kp, 128, 2 * N, 1.5, 0.0, 0)
+        assert int(cnt.sum()) == total == int(mask.sum())
+        T = N // 128
+        # block density of plain causal attention, Section "Segmented Permutation for Causal Attention"
+        assert abs(cnt.sum() / T ** 2 - (T + 1) / (2 * T)) < 1e-12
+
+
+def test_lists_agree_with_mask(oracle):
+    rng = np.random.default_rng(9)
+    N, d = 200, 8
+    Qp = rng.standard_normal((1, 3, N, d)).astype(np.float32)
+    Kp = rng.standard_normal((1, 1, N, d)).astype(np.float32)
+    mask, cnt, cols = oracle.block_mask(Qp, Kp, 16, 64, 0.7, 0.0, 1)
+    T = mask.shape[-1]
+    for h in range(3):
+        for i in range(T):
+            want = np.flatnonzero(mask[0, h, i])
+            assert cnt[0, h, i] == want.size
+            np.testing.assert_array_equal(cols[0, h, i, :want.size], want)
+            assert (cols[0, h, i, want.size:] == -1).all()
