@@ -1,0 +1,171 @@
+/*
+ * pbs.h -- C ABI of the MI355X-native PBS-Attn prefill path.
+ *
+ * PBS-Attn = Permuted Block-Sparse Attention (arXiv 2510.21270).  One prefill
+ * attention forward pass is Algorithm 1 of the paper:
+ *
+ *   pbs_key_scores      Eq. 4   global importance score of every key
+ *   pbs_segment_permute Eq. 5   per-segment descending argsort + K', V' = P_pi K, P_pi V
+ *   pbs_block_mask      Alg. 2  mean-pooled cumulative-mass block selection on (Q', K')
+ *   pbs_attn_fwd        Alg. 1  online-softmax attention over the selected blocks only
+ *   pbs_unpermute       Alg. 1  O = P_sigma^T O'   (Theorem 1)
+ *
+ * General conventions
+ *   - Every tensor pointer is a DEVICE pointer to caller-owned, contiguous,
+ *     row-major memory, 16-byte aligned.  The library never allocates, frees
+ *     or synchronises; all work is enqueued on `stream` (a hipStream_t passed
+ *     as void*, NULL = the default stream) and is complete when the stream is.
+ *   - `pbs_problem` itself is a HOST pointer and is read during the call only.
+ *   - Arguments are validated on the host before anything is launched; a bad
+ *     call returns a status and enqueues nothing.  A failed launch returns
+ *     PBS_ERR_HIP.  Nothing throws or aborts.
+ *   - Q is [batch, h_q, n, d]; K and V are [batch, h_kv, n, d]; h_q % h_kv == 0
+ *     and query head h reads kv head h / (h_q / h_kv)  (grouped-query attention;
+ *     one permutation per kv head, the "shared permutation strategy" of the
+ *     appendix "GQA Handling"; the replicated default of the paper is the case
+ *     h_kv == h_q).
+ *   - T = ceil(n / block) blocks; segment % block == 0; R = segment / block;
+ *     G = floor(n / segment) full segments; tokens at or beyond G * segment are
+ *     never permuted (Section "Segmented Permutation for Causal Attention").
+ *   - Index vectors are in gather form with absolute positions: slot p of a
+ *     permuted tensor holds original token idx[p], and idx maps every segment
+ *     onto itself.
+ *   - K' ("Kp") keeps the [batch, h_kv, n, d] layout.  V' is kept as "Vt":
+ *     [batch, h_kv, T, d, block], i.e. every key block stored transposed, the
+ *     slots past n in the last block zero-filled.  Vt is produced by
+ *     pbs_segment_permute and consumed by pbs_attn_fwd; pbs_vt_bytes gives its
+ *     size.
+ *   - Supported: dtype PBS_BF16 or PBS_F32; d in {64, 128}; block in
+ *     {16, 32, 64, 128}; segment <= 4096; T <= 4096; any n >= 1.  The matrix-core
+ *     attention kernel serves PBS_BF16 with d = 128 and block in {64, 128};
+ *     every other supported combination runs on fp32 vector arithmetic.
+ *   - Results are deterministic: the same inputs give bit-identical outputs.
+ */
+#ifndef PBS_H
+#define PBS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PBS_OK = 0,
+    PBS_ERR_NULL = 1,        /* a required pointer is NULL */
+    PBS_ERR_SHAPE = 2,       /* inconsistent sizes (h_q % h_kv, segment % block, n < 1, ...) */
+    PBS_ERR_UNSUPPORTED = 3, /* valid problem outside the supported set listed above */
+    PBS_ERR_WORKSPACE = 4,   /* ws_bytes smaller than pbs_workspace_bytes(), or ws misaligned */
+    PBS_ERR_HIP = 5          /* a kernel launch failed */
+} pbs_status;
+
+typedef enum { PBS_F32 = 0, PBS_BF16 = 1 } pbs_dtype;
+
+enum { PBS_FLAG_FORCE_FIRST_BLOCK = 1u };
+
+typedef enum {
+    PBS_STAGE_KEY_SCORES = 1,
+    PBS_STAGE_SEGMENT_PERMUTE = 2,
+    PBS_STAGE_BLOCK_MASK = 3,
+    PBS_STAGE_ATTN_FWD = 4,
+    PBS_STAGE_UNPERMUTE = 5
+} pbs_stage;
+
+typedef struct {
+    int32_t batch, h_q, h_kv, n, d;
+    int32_t block;    /* B of the paper */
+    int32_t segment;  /* S of the paper */
+    int32_t dtype;    /* pbs_dtype of Q, K, V, K', Vt, O', O */
+    float tau;        /* mass threshold of Alg. 2, compared as (double)tau */
+    float scale;      /* logit scale; 0 means 1/sqrt(d) */
+    uint32_t flags;   /* PBS_FLAG_* */
+} pbs_problem;
+
+/* Static string for a status code (never NULL). */
+const char *pbs_status_string(pbs_status st);
+
+/* PBS_OK when the problem is inside the supported set, else the status every stage would return. */
+pbs_status pbs_validate(const pbs_problem *p);
+
+/* Bytes of scratch a stage needs in `ws` (256-byte aligned device memory); 0 for an invalid problem. */
+size_t pbs_workspace_bytes(const pbs_problem *p, int stage);
+
+/* Bytes of the Vt tensor: batch * h_kv * T * d * block elements of the problem's dtype. */
+size_t pbs_vt_bytes(const pbs_problem *p);
+
+/*
+ * Eq. 4, with the queries of a GQA group averaged (appendix "GQA Handling"):
+ *   Qhat = mean over the group's query heads of the last min(block, n) rows of Q,
+ *   scores = mean_rows( softmax_over_all_n_keys( Qhat K^T * scale ) ).
+ * No causal mask (Eq. 4 has none).  Q [batch,h_q,n,d] (only the last rows are read), K [batch,h_kv,n,d]
+ * -> scores [batch,h_kv,n] float32.  bf16 inputs: matrix cores with an fp32 accumulator and a two-term
+ * split of Qhat; fp32 inputs: fp64 accumulation.
+ */
+pbs_status pbs_key_scores(const pbs_problem *p, const void *Q, const void *K, float *scores,
+                          void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Eq. 5 inside each full segment: kidx[g*S + t] = g*S + (position of the t-th largest score of segment g),
+ * equal scores in ascending position (stable), tail positions kept (identity).  Then Algorithm 1's first
+ * step for keys and values: Kp[slot] = K[kidx[slot]], Vt = block-transposed V[kidx[.]].
+ *   scores [batch,h_kv,n] float32, or NULL for the identity permutation (the unpermuted MeanPooling
+ *     baseline of the appendix "Block Selection in PBS-Attn": K' = K, V' = V).  NaN scores are not supported.
+ *   kidx   [batch,h_kv,n] int32, written.
+ *   Kp, Vt written; pass both NULL to compute kidx only (K and V may then be NULL too).
+ */
+pbs_status pbs_segment_permute(const pbs_problem *p, const float *scores, const void *K, const void *V,
+                               int32_t *kidx, void *Kp, void *Vt, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Algorithm 1's first step for any [batch, heads, n, d] tensor: Xp[slot] = X[idx[slot]] (Q' = P_sigma Q for a
+ * caller-supplied segment-wise sigma; the paper's main setting P_sigma = I needs no call).
+ * idx [batch,heads,n] int32 with values in [0, n); an out-of-range entry yields a zero row.
+ */
+pbs_status pbs_permute_rows(const pbs_problem *p, int32_t heads, const void *X, const int32_t *idx, void *Xp,
+                            void *stream);
+
+/*
+ * Algorithm 2 on the permuted (Q', K'), per query head:
+ *   block means (valid rows only in a partial last block);
+ *   a_i = softmax_j(Qbar_i . Kbar_j * scale) over the columns the extended causal mask C admits:
+ *         j < (g(i)+1)*R for a query block inside full segment g(i), j <= i past the last full segment;
+ *   stable descending sort (ties: lowest j), cumulative sum, k = min({t : c[t] >= tau} U {n_i}), first k kept.
+ * All of this is IEEE fp64 so that the discrete result does not depend on the machine.  Then the blocks of the
+ * query block's own segment are switched on (Section "Effect of Segment Size": they cannot be skipped); past the
+ * last full segment only the diagonal block; and block 0 when PBS_FLAG_FORCE_FIRST_BLOCK is set (Section
+ * "Baselines").  Forced blocks do not change k.
+ *   mask_bits [batch,h_q,T,ceil(T/64)] uint64, bit (j & 63) of word (j >> 6) of row i = M[i][j];
+ *   row_cnt   [batch,h_q,T] int32; col_idx [batch,h_q,T,T] int32, the first row_cnt[i] entries of row i are the
+ *   selected j ascending, the rest is left untouched.
+ */
+pbs_status pbs_block_mask(const pbs_problem *p, const void *Qp, const void *Kp, uint64_t *mask_bits,
+                          int32_t *row_cnt, int32_t *col_idx, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Algorithm 1's main loop: for every query block i, over the listed key blocks only (a block that is not
+ * listed leaves the running (O, m, l) untouched): S = Q'_i K'_j^T * scale, online softmax, O'_i = diag(l)^-1 O.
+ * Inside the query block's own segment, and in the unpermuted tail, entry (row, col) takes part only if the
+ * key's original position is not after the query's: kidx[j*block+col] <= qidx[i*block+row]; key slots >= n never
+ * take part.  Listed blocks outside the columns C admits are ignored.  A query row that sees no key at all gets
+ * a zero output row and lse = -inf (cannot happen when the diagonal block is listed).
+ *   Qp [batch,h_q,n,d]; Kp [batch,h_kv,n,d]; Vt as above; qidx [batch,h_q,n] or NULL (identity);
+ *   kidx [batch,h_kv,n]; row_cnt, col_idx as written by pbs_block_mask (any order of the listed blocks is
+ *   accepted); Op [batch,h_q,n,d] written; lse [batch,h_q,n] float32 or NULL: log-sum-exp of the visible,
+ *   listed logits of every query row.
+ */
+pbs_status pbs_attn_fwd(const pbs_problem *p, const void *Qp, const void *Kp, const void *Vt,
+                        const int32_t *qidx, const int32_t *kidx, const int32_t *row_cnt, const int32_t *col_idx,
+                        void *Op, float *lse, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Algorithm 1's last step (Theorem 1): O[qidx[slot]] = Op[slot].  qidx NULL (P_sigma = I, the paper's main
+ * setting) makes this a plain copy, or nothing at all when O == Op.  Op, O [batch,h_q,n,d]; O must not
+ * partially overlap Op.
+ */
+pbs_status pbs_unpermute(const pbs_problem *p, const void *Op, const int32_t *qidx, void *O, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PBS_H */

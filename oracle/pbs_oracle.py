@@ -212,7 +212,7 @@ def pipeline(Q, K, V, block, segment, tau, scale=0.0, flags=0, qidx=None, score_
     Vp = gather_rows(V, kidx)
     Qp = gather_rows(Q, qidx) if qidx is not None else np.ascontiguousarray(Q, dtype=np.float32)
     mask, row_cnt, col_idx = block_mask(Qp, Kp, block, segment, tau, scale, flags)
-    Op = attn_fwd(Qp, Kp, Vp, qidx, kidx, row_cnt, col_idx, block, scale)
+    Op, lse = attn_fwd(Qp, Kp, Vp, qidx, kidx, row_cnt, col_idx, block, scale, want_lse=True)
     O = scatter_rows(Op, qidx)
     return dict(s=s, s_handoff=s_h, kidx=kidx, Kp=Kp, Vp=Vp, Qp=Qp, mask=mask, row_cnt=row_cnt,
-                col_idx=col_idx, Op=Op, O=O)
+                col_idx=col_idx, Op=Op, lse=lse, O=O)

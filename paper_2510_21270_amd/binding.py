@@ -1,0 +1,203 @@
+"""Thin ctypes binding of libpbs.so (include/pbs.h).  Argument marshalling only.
+
+PyTorch is used for device memory and streams; every step of the path runs in the library's HIP kernels.
+The functions carry the names of the C entry points.  There is no CPU fallback: if the library is missing
+or a call fails, an exception is raised.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpbs.so")
+_lib = None
+
+PBS_F32, PBS_BF16 = 0, 1
+STAGE_KEY_SCORES, STAGE_SEGMENT_PERMUTE, STAGE_BLOCK_MASK, STAGE_ATTN_FWD, STAGE_UNPERMUTE = 1, 2, 3, 4, 5
+FLAG_FORCE_FIRST_BLOCK = 1
+
+EXPORTS = ["pbs_status_string", "pbs_validate", "pbs_workspace_bytes", "pbs_vt_bytes", "pbs_key_scores",
+           "pbs_segment_permute", "pbs_permute_rows", "pbs_block_mask", "pbs_attn_fwd", "pbs_unpermute"]
+
+
+class PbsError(RuntimeError):
+    pass
+
+
+class pbs_problem(ctypes.Structure):
+    _fields_ = [("batch", ctypes.c_int32), ("h_q", ctypes.c_int32), ("h_kv", ctypes.c_int32), ("n", ctypes.c_int32),
+                ("d", ctypes.c_int32), ("block", ctypes.c_int32), ("segment", ctypes.c_int32),
+                ("dtype", ctypes.c_int32), ("tau", ctypes.c_float), ("scale", ctypes.c_float),
+                ("flags", ctypes.c_uint32)]
+
+
+def load_library():
+    """Load libpbs.so built in-tree (python -m paper_2510_21270_amd.build).  Fails loudly when it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise PbsError("libpbs.so not found at %s: build it with `python -m paper_2510_21270_amd.build`" % LIB_PATH)
+        lib = ctypes.CDLL(LIB_PATH)
+        P, V, Z = ctypes.POINTER(pbs_problem), ctypes.c_void_p, ctypes.c_size_t
+        lib.pbs_status_string.restype = ctypes.c_char_p
+        lib.pbs_status_string.argtypes = [ctypes.c_int]
+        lib.pbs_validate.argtypes = [P]
+        lib.pbs_workspace_bytes.restype = Z
+        lib.pbs_workspace_bytes.argtypes = [P, ctypes.c_int]
+        lib.pbs_vt_bytes.restype = Z
+        lib.pbs_vt_bytes.argtypes = [P]
+        lib.pbs_key_scores.argtypes = [P, V, V, V, V, Z, V]
+        lib.pbs_segment_permute.argtypes = [P, V, V, V, V, V, V, V, Z, V]
+        lib.pbs_permute_rows.argtypes = [P, ctypes.c_int32, V, V, V, V]
+        lib.pbs_block_mask.argtypes = [P, V, V, V, V, V, V, Z, V]
+        lib.pbs_attn_fwd.argtypes = [P, V, V, V, V, V, V, V, V, V, V, Z, V]
+        lib.pbs_unpermute.argtypes = [P, V, V, V, V]
+        _lib = lib
+    return _lib
+
+
+def problem(batch, h_q, h_kv, n, d, block, segment, dtype, tau=0.9, scale=0.0, flags=0):
+    code = {"bf16": PBS_BF16, "f32": PBS_F32, torch.bfloat16: PBS_BF16, torch.float32: PBS_F32}[dtype]
+    return pbs_problem(batch, h_q, h_kv, n, d, block, segment, code, tau, scale, flags)
+
+
+def torch_dtype(p):
+    return torch.bfloat16 if p.dtype == PBS_BF16 else torch.float32
+
+
+def _check(st, what):
+    if st != 0:
+        raise PbsError("%s: %s (status %d)" % (what, load_library().pbs_status_string(st).decode(), st))
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def validate(p):
+    return load_library().pbs_validate(ctypes.byref(p))
+
+
+def workspace_bytes(p, stage):
+    return int(load_library().pbs_workspace_bytes(ctypes.byref(p), stage))
+
+
+def vt_bytes(p):
+    return int(load_library().pbs_vt_bytes(ctypes.byref(p)))
+
+
+def T_of(p):
+    return -(-p.n // p.block)
+
+
+def alloc_workspace(p, stage, device="cuda"):
+    nbytes = workspace_bytes(p, stage)
+    return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)   # torch allocations are 512-B aligned
+
+
+def alloc_vt(p, device="cuda"):
+    return torch.empty((p.batch, p.h_kv, T_of(p), p.d, p.block), dtype=torch_dtype(p), device=device)
+
+
+def _ws_args(p, stage, ws):
+    if ws is None:
+        ws = alloc_workspace(p, stage)
+    return ws, _ptr(ws), ws.numel()
+
+
+def key_scores(p, Q, K, scores=None, ws=None):
+    if scores is None:
+        scores = torch.empty((p.batch, p.h_kv, p.n), dtype=torch.float32, device=K.device)
+    ws, wp, wn = _ws_args(p, STAGE_KEY_SCORES, ws)
+    _check(load_library().pbs_key_scores(ctypes.byref(p), _ptr(Q), _ptr(K), _ptr(scores), wp, wn, _stream()),
+           "pbs_key_scores")
+    return scores
+
+
+def segment_permute(p, scores, K, V, kidx=None, Kp=None, Vt=None, indices_only=False):
+    dev = (K if K is not None else scores).device
+    if kidx is None:
+        kidx = torch.empty((p.batch, p.h_kv, p.n), dtype=torch.int32, device=dev)
+    if not indices_only:
+        if Kp is None:
+            Kp = torch.empty_like(K)
+        if Vt is None:
+            Vt = alloc_vt(p, dev)
+    _check(load_library().pbs_segment_permute(ctypes.byref(p), _ptr(scores), _ptr(K), _ptr(V), _ptr(kidx), _ptr(Kp),
+                                              _ptr(Vt), None, 0, _stream()), "pbs_segment_permute")
+    return kidx, Kp, Vt
+
+
+def permute_rows(p, X, idx, Xp=None):
+    if Xp is None:
+        Xp = torch.empty_like(X)
+    _check(load_library().pbs_permute_rows(ctypes.byref(p), X.shape[1], _ptr(X), _ptr(idx), _ptr(Xp), _stream()),
+           "pbs_permute_rows")
+    return Xp
+
+
+def block_mask(p, Qp, Kp, mask_bits=None, row_cnt=None, col_idx=None, ws=None):
+    T = T_of(p)
+    dev = Qp.device
+    if mask_bits is None:
+        mask_bits = torch.empty((p.batch, p.h_q, T, (T + 63) // 64), dtype=torch.int64, device=dev)
+    if row_cnt is None:
+        row_cnt = torch.empty((p.batch, p.h_q, T), dtype=torch.int32, device=dev)
+    if col_idx is None:
+        col_idx = torch.empty((p.batch, p.h_q, T, T), dtype=torch.int32, device=dev)
+    ws, wp, wn = _ws_args(p, STAGE_BLOCK_MASK, ws)
+    _check(load_library().pbs_block_mask(ctypes.byref(p), _ptr(Qp), _ptr(Kp), _ptr(mask_bits), _ptr(row_cnt),
+                                         _ptr(col_idx), wp, wn, _stream()), "pbs_block_mask")
+    return mask_bits, row_cnt, col_idx
+
+
+def attn_fwd(p, Qp, Kp, Vt, qidx, kidx, row_cnt, col_idx, Op=None, lse=None, want_lse=False):
+    if Op is None:
+        Op = torch.empty_like(Qp)
+    if lse is None and want_lse:
+        lse = torch.empty((p.batch, p.h_q, p.n), dtype=torch.float32, device=Qp.device)
+    _check(load_library().pbs_attn_fwd(ctypes.byref(p), _ptr(Qp), _ptr(Kp), _ptr(Vt), _ptr(qidx), _ptr(kidx),
+                                       _ptr(row_cnt), _ptr(col_idx), _ptr(Op), _ptr(lse), None, 0, _stream()),
+           "pbs_attn_fwd")
+    return (Op, lse) if want_lse else Op
+
+
+def unpermute(p, Op, qidx, O=None):
+    if O is None:
+        O = Op if qidx is None else torch.empty_like(Op)
+    _check(load_library().pbs_unpermute(ctypes.byref(p), _ptr(Op), _ptr(qidx), _ptr(O), _stream()), "pbs_unpermute")
+    return O
+
+
+class Pipeline:
+    """Algorithm 1 end to end on preallocated buffers: the five library calls, nothing else."""
+
+    def __init__(self, p, device="cuda", use_sigma=False):
+        self.p = p
+        T, dt = T_of(p), torch_dtype(p)
+        self.scores = torch.empty((p.batch, p.h_kv, p.n), dtype=torch.float32, device=device)
+        self.kidx = torch.empty((p.batch, p.h_kv, p.n), dtype=torch.int32, device=device)
+        self.Kp = torch.empty((p.batch, p.h_kv, p.n, p.d), dtype=dt, device=device)
+        self.Vt = alloc_vt(p, device)
+        self.mask_bits = torch.empty((p.batch, p.h_q, T, (T + 63) // 64), dtype=torch.int64, device=device)
+        self.row_cnt = torch.empty((p.batch, p.h_q, T), dtype=torch.int32, device=device)
+        self.col_idx = torch.empty((p.batch, p.h_q, T, T), dtype=torch.int32, device=device)
+        self.Op = torch.empty((p.batch, p.h_q, p.n, p.d), dtype=dt, device=device)
+        self.O = torch.empty_like(self.Op) if use_sigma else self.Op
+        self.Qp = torch.empty_like(self.Op) if use_sigma else None
+        self.ws1 = alloc_workspace(p, STAGE_KEY_SCORES, device)
+        self.ws3 = alloc_workspace(p, STAGE_BLOCK_MASK, device)
+
+    def run(self, Q, K, V, qidx=None):
+        p = self.p
+        key_scores(p, Q, K, self.scores, self.ws1)
+        segment_permute(p, self.scores, K, V, self.kidx, self.Kp, self.Vt)
+        Qp = Q if qidx is None else permute_rows(p, Q, qidx, self.Qp)
+        block_mask(p, Qp, self.Kp, self.mask_bits, self.row_cnt, self.col_idx, self.ws3)
+        attn_fwd(p, Qp, self.Kp, self.Vt, qidx, self.kidx, self.row_cnt, self.col_idx, self.Op)
+        return unpermute(p, self.Op, qidx, self.O)

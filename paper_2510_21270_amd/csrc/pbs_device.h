@@ -1,0 +1,88 @@
+// Device-side helpers shared by the PBS-Attn kernels (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/pbs.h"
+
+namespace pbs {
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
+typedef uint32_t uintx2 __attribute__((ext_vector_type(2)));
+
+constexpr int kWave = 64;
+
+// Geometry derived from a pbs_problem, computed once on the host and passed by value to kernels.
+struct Geo {
+    int batch, h_q, h_kv, r, n, d, block, segment;
+    int T;      // ceil(n / block)
+    int R;      // blocks per segment
+    int G;      // full segments
+    float scale;
+    double tau;
+    unsigned flags;
+};
+
+__host__ __device__ inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+// number of key blocks the extended causal mask lets query block i see
+__host__ __device__ inline int allowed_cols(int i, const Geo &g)
+{
+    int s = i / g.R;
+    if (s < g.G) {
+        int v = (s + 1) * g.R;
+        return v < g.T ? v : g.T;
+    }
+    return i + 1;
+}
+
+// first key block of query block i whose entries need the token-level position test
+__host__ __device__ inline int first_masked_col(int i, const Geo &g)
+{
+    int s = i / g.R;
+    return s < g.G ? s * g.R : i;
+}
+
+template <typename T> struct ElemTraits;
+template <> struct ElemTraits<float> {
+    __device__ static inline float to_float(float v) { return v; }
+    __device__ static inline float from_float(float v) { return v; }
+};
+template <> struct ElemTraits<bf16_t> {
+    __device__ static inline float to_float(bf16_t v) { return (float)v; }
+    __device__ static inline bf16_t from_float(float v) { return (bf16_t)v; }
+};
+
+__device__ inline float wave_max(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+__device__ inline float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ inline double wave_max(double v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmax(v, __shfl_xor(v, o, 64));
+    return v;
+}
+__device__ inline double wave_sum(double v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+}  // namespace pbs

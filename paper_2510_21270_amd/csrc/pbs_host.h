@@ -1,0 +1,65 @@
+// Host-side validation and geometry shared by the C-ABI entry points.
+#pragma once
+#include <math.h>
+
+#include "pbs_device.h"
+
+namespace pbs {
+
+constexpr int kMaxSegment = 4096;
+constexpr int kMaxT = 4096;
+constexpr size_t kWsAlign = 256;
+
+inline size_t elem_size(int dtype) { return dtype == PBS_BF16 ? 2 : 4; }
+
+inline pbs_status validate(const pbs_problem *p)
+{
+    if (!p) return PBS_ERR_NULL;
+    if (p->batch < 1 || p->h_q < 1 || p->h_kv < 1 || p->n < 1 || p->d < 1 || p->block < 1 || p->segment < 1)
+        return PBS_ERR_SHAPE;
+    if (p->h_q % p->h_kv != 0 || p->segment % p->block != 0) return PBS_ERR_SHAPE;
+    if (!(p->tau == p->tau) || !(p->scale == p->scale) || p->scale < 0.0f || isinf(p->scale)) return PBS_ERR_SHAPE;
+    if (p->dtype != PBS_F32 && p->dtype != PBS_BF16) return PBS_ERR_UNSUPPORTED;
+    if (p->d != 64 && p->d != 128) return PBS_ERR_UNSUPPORTED;
+    if (p->block != 16 && p->block != 32 && p->block != 64 && p->block != 128) return PBS_ERR_UNSUPPORTED;
+    if (p->segment > kMaxSegment) return PBS_ERR_UNSUPPORTED;
+    if ((p->n + p->block - 1) / p->block > kMaxT) return PBS_ERR_UNSUPPORTED;
+    // every tensor is indexed with 64-bit offsets, but row counts must fit an int
+    if ((long long)p->batch * p->h_q * (long long)p->n > 0x7fffffffLL) return PBS_ERR_UNSUPPORTED;
+    if ((long long)p->batch * p->h_q > 65535) return PBS_ERR_UNSUPPORTED;   // heads ride on gridDim.y
+    return PBS_OK;
+}
+
+inline Geo make_geo(const pbs_problem *p)
+{
+    Geo g;
+    g.batch = p->batch; g.h_q = p->h_q; g.h_kv = p->h_kv; g.r = p->h_q / p->h_kv;
+    g.n = p->n; g.d = p->d; g.block = p->block; g.segment = p->segment;
+    g.T = (p->n + p->block - 1) / p->block;
+    g.R = p->segment / p->block;
+    g.G = p->n / p->segment;
+    g.scale = p->scale > 0.0f ? p->scale : (float)(1.0 / sqrt((double)p->d));
+    g.tau = (double)p->tau;
+    g.flags = p->flags;
+    return g;
+}
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+inline bool aligned16(const void *ptr) { return (reinterpret_cast<uintptr_t>(ptr) & 15u) == 0; }
+
+inline pbs_status check_ws(const pbs_problem *p, int stage, const void *ws, size_t ws_bytes)
+{
+    size_t need = pbs_workspace_bytes(p, stage);
+    if (need == 0) return PBS_OK;
+    if (!ws) return PBS_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(ws) & (kWsAlign - 1)) != 0 || ws_bytes < need) return PBS_ERR_WORKSPACE;
+    return PBS_OK;
+}
+
+inline pbs_status launch_status()
+{
+    return hipGetLastError() == hipSuccess ? PBS_OK : PBS_ERR_HIP;
+}
+
+}  // namespace pbs

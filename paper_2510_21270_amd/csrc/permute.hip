@@ -1,0 +1,226 @@
+// Segmented permutation (Eq. 5 + Algorithm 1's first and last steps): per-segment stable descending
+// argsort of the key scores, row gathers for K' and Q', the block-transposed gather for V', and the
+// inverse row scatter for the output.  Pure integer/compare and copy work: bound by HBM.
+#include "pbs_host.h"
+
+namespace pbs {
+
+// ---------------------------------------------------------------------------------------------
+// One workgroup sorts one segment in LDS.  Key = (~orderable(score)) << 32 | position-in-segment, so an
+// ascending 64-bit bitonic sort yields descending score with ties in ascending position.  -0.0 is
+// folded onto +0.0 first so that the bit order agrees with the arithmetic order.
+// grid = (G + 1, batch*h_kv); workgroup G writes the identity for the unpermuted tail.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void segment_argsort_kernel(const float *__restrict__ scores,
+                                                              int32_t *__restrict__ kidx, int n, int segment,
+                                                              int G, int p2)
+{
+    extern __shared__ uint64_t keys[];
+    const int g = blockIdx.x;
+    const size_t base = (size_t)blockIdx.y * n;
+    if (g >= G) {
+        for (int p = G * segment + threadIdx.x; p < n; p += blockDim.x) kidx[base + p] = p;
+        return;
+    }
+    const float *s = scores + base + (size_t)g * segment;
+    for (int t = threadIdx.x; t < p2; t += blockDim.x) {
+        uint64_t key = ~0ull;
+        if (t < segment) {
+            float f = s[t] + 0.0f;
+            uint32_t u = __float_as_uint(f);
+            u = (u & 0x80000000u) ? ~u : (u | 0x80000000u);   // ascending in u == ascending in f
+            key = ((uint64_t)(~u) << 32) | (uint32_t)t;
+        }
+        keys[t] = key;
+    }
+    __syncthreads();
+    for (int k = 2; k <= p2; k <<= 1) {
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            for (int t = threadIdx.x; t < (p2 >> 1); t += blockDim.x) {
+                // t-th compare-exchange pair of this stage: insert a zero bit at position log2(j)
+                const int lo = t & (j - 1);
+                const int a = ((t - lo) << 1) | lo;
+                const int b = a | j;
+                const bool asc = (a & k) == 0;
+                const uint64_t ka = keys[a], kb = keys[b];
+                if ((ka > kb) == asc) { keys[a] = kb; keys[b] = ka; }
+            }
+            __syncthreads();
+        }
+    }
+    for (int t = threadIdx.x; t < segment; t += blockDim.x)
+        kidx[base + (size_t)g * segment + t] = g * segment + (int32_t)(keys[t] & 0xffffffffu);
+}
+
+__global__ __launch_bounds__(256) void iota_kernel(int32_t *__restrict__ idx, int n, size_t total)
+{
+    for (size_t p = (size_t)blockIdx.x * blockDim.x + threadIdx.x; p < total; p += (size_t)gridDim.x * blockDim.x)
+        idx[p] = (int32_t)(p % (size_t)n);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Row gather / scatter in 16-byte chunks; cpr = chunks per row (a power of two).
+// SCATTER = false: dst[row] = src[head(row), idx[row]]     (X' = P X)
+// SCATTER = true : dst[head(row), idx[row]] = src[row]     (O = P^T O')
+// idx == NULL is the identity.  An index outside [0, n) gives a zero row (gather) or is dropped (scatter).
+// ---------------------------------------------------------------------------------------------
+template <bool SCATTER>
+__global__ __launch_bounds__(256) void move_rows_kernel(const uintx4 *__restrict__ src,
+                                                        const int32_t *__restrict__ idx,
+                                                        uintx4 *__restrict__ dst, int n, int cpr_log2)
+{
+    // grid = (x, nbh): blockIdx.y is the head, x strides over that head's n * cpr chunks
+    const size_t head = (size_t)blockIdx.y * n;
+    const uint32_t chunks = (uint32_t)n << cpr_log2;
+    const uint32_t cmask = (1u << cpr_log2) - 1u;
+    const uintx4 *hsrc = src + (head << cpr_log2);
+    uintx4 *hdst = dst + (head << cpr_log2);
+    const int32_t *hidx = idx ? idx + head : nullptr;
+    for (uint32_t c = blockIdx.x * blockDim.x + threadIdx.x; c < chunks; c += gridDim.x * blockDim.x) {
+        const uint32_t row = c >> cpr_log2, cc = c & cmask;
+        const int32_t other = hidx ? hidx[row] : (int32_t)row;
+        const bool ok = other >= 0 && other < n;
+        if (SCATTER) {
+            if (ok) hdst[((uint32_t)other << cpr_log2) + cc] = hsrc[c];
+        } else {
+            uintx4 v = {0u, 0u, 0u, 0u};
+            if (ok) v = hsrc[((uint32_t)other << cpr_log2) + cc];
+            hdst[c] = v;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// V' in the block-transposed layout Vt[bh][j][e][c] = V[bh][kidx[j*block + c]][e] (zero for slots >= n).
+// One workgroup per (key block j, bh): gathered rows go to LDS with coalesced 16-byte reads, the tile is
+// read back column-wise and leaves as full rows of Vt (coalesced 16-byte writes).
+// E = element type (2 or 4 bytes); VEC = elements per 16-byte chunk.
+// ---------------------------------------------------------------------------------------------
+template <typename E>
+__global__ __launch_bounds__(256) void gather_vt_kernel(const E *__restrict__ V, const int32_t *__restrict__ kidx,
+                                                        E *__restrict__ Vt, int n, int d, int block, int T)
+{
+    constexpr int VEC = 16 / sizeof(E);
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    E *tile = reinterpret_cast<E *>(smem_raw);            // [block][d + VEC]
+    const int ld = d + VEC;
+    const int j = blockIdx.x;
+    const size_t bh = blockIdx.y;
+    const int cpr = d / VEC;
+    typedef E vec_t __attribute__((ext_vector_type(VEC)));
+    for (int c = threadIdx.x; c < block * cpr; c += blockDim.x) {
+        const int row = c / cpr, cc = c % cpr;
+        const int slot = j * block + row;
+        vec_t v = {};
+        if (slot < n) {
+            const int32_t src = kidx ? kidx[bh * n + slot] : slot;
+            if (src >= 0 && src < n) v = *reinterpret_cast<const vec_t *>(V + (bh * n + src) * (size_t)d + cc * VEC);
+        }
+        *reinterpret_cast<vec_t *>(tile + row * ld + cc * VEC) = v;
+    }
+    __syncthreads();
+    const int gpr = block / VEC;                           // 16-byte groups per Vt row
+    E *out = Vt + (bh * T + j) * (size_t)d * block;
+    for (int c = threadIdx.x; c < d * gpr; c += blockDim.x) {
+        const int e = c / gpr, kg = c % gpr;
+        vec_t v;
+#pragma unroll
+        for (int u = 0; u < VEC; ++u) v[u] = tile[(kg * VEC + u) * ld + e];
+        *reinterpret_cast<vec_t *>(out + (size_t)e * block + kg * VEC) = v;
+    }
+}
+
+static int ilog2(int v) { int l = 0; while ((1 << l) < v) ++l; return l; }
+
+static int grid_for(size_t items, int per_block)
+{
+    size_t b = (items + per_block - 1) / per_block;
+    const size_t cap = 256 * 32;                          // 32 workgroups per CU is plenty for a copy
+    if (b > cap) b = cap;
+    if (b < 1) b = 1;
+    return (int)b;
+}
+
+// grid for move_rows_kernel: enough workgroups to fill the chip, each thread moving a few chunks
+static dim3 move_grid(int n, int cpr, int nbh)
+{
+    const size_t chunks = (size_t)n * cpr;
+    size_t bx = (chunks + 256 * 4 - 1) / (256 * 4);
+    const size_t cap = (size_t)(256 * 32 + nbh - 1) / nbh;
+    if (bx > cap) bx = cap;
+    if (bx < 1) bx = 1;
+    return dim3((unsigned)bx, (unsigned)nbh);
+}
+
+}  // namespace pbs
+
+using namespace pbs;
+
+extern "C" pbs_status pbs_segment_permute(const pbs_problem *p, const float *scores, const void *K, const void *V,
+                                          int32_t *kidx, void *Kp, void *Vt, void *ws, size_t ws_bytes,
+                                          void *stream)
+{
+    (void)ws; (void)ws_bytes;
+    pbs_status st = validate(p);
+    if (st != PBS_OK) return st;
+    if (!kidx) return PBS_ERR_NULL;
+    if ((Kp == nullptr) != (Vt == nullptr)) return PBS_ERR_NULL;
+    if (Kp && (!K || !V)) return PBS_ERR_NULL;
+    if (Kp && (!aligned16(K) || !aligned16(V) || !aligned16(Kp) || !aligned16(Vt))) return PBS_ERR_SHAPE;
+    const Geo g = make_geo(p);
+    hipStream_t s = (hipStream_t)stream;
+    const int nbh = g.batch * g.h_kv;
+    if (scores) {
+        int p2 = 1;
+        while (p2 < g.segment) p2 <<= 1;
+        hipLaunchKernelGGL(segment_argsort_kernel, dim3(g.G + 1, nbh), dim3(256), (size_t)p2 * sizeof(uint64_t), s,
+                           scores, kidx, g.n, g.segment, g.G, p2);
+    } else {
+        const size_t total = (size_t)nbh * g.n;
+        hipLaunchKernelGGL(iota_kernel, dim3(grid_for(total, 256)), dim3(256), 0, s, kidx, g.n, total);
+    }
+    if ((st = launch_status()) != PBS_OK) return st;
+    if (!Kp) return PBS_OK;
+    const size_t es = elem_size(p->dtype);
+    const int cpr = (int)(g.d * es / 16);
+    hipLaunchKernelGGL(move_rows_kernel<false>, move_grid(g.n, cpr, nbh), dim3(256), 0, s,
+                       (const uintx4 *)K, (const int32_t *)kidx, (uintx4 *)Kp, g.n, ilog2(cpr));
+    if ((st = launch_status()) != PBS_OK) return st;
+    if (p->dtype == PBS_BF16) {
+        const size_t lds = (size_t)g.block * (g.d + 8) * 2;
+        hipLaunchKernelGGL(gather_vt_kernel<uint16_t>, dim3(g.T, nbh), dim3(256), lds, s, (const uint16_t *)V,
+                           (const int32_t *)kidx, (uint16_t *)Vt, g.n, g.d, g.block, g.T);
+    } else {
+        const size_t lds = (size_t)g.block * (g.d + 4) * 4;
+        hipLaunchKernelGGL(gather_vt_kernel<uint32_t>, dim3(g.T, nbh), dim3(256), lds, s, (const uint32_t *)V,
+                           (const int32_t *)kidx, (uint32_t *)Vt, g.n, g.d, g.block, g.T);
+    }
+    return launch_status();
+}
+
+extern "C" pbs_status pbs_permute_rows(const pbs_problem *p, int32_t heads, const void *X, const int32_t *idx,
+                                       void *Xp, void *stream)
+{
+    pbs_status st = validate(p);
+    if (st != PBS_OK) return st;
+    if (!X || !idx || !Xp) return PBS_ERR_NULL;
+    if (heads < 1) return PBS_ERR_SHAPE;
+    if (!aligned16(X) || !aligned16(Xp) || X == Xp) return PBS_ERR_SHAPE;
+    const int cpr = (int)(p->d * elem_size(p->dtype) / 16);
+    hipLaunchKernelGGL(move_rows_kernel<false>, move_grid(p->n, cpr, p->batch * heads), dim3(256), 0,
+                       (hipStream_t)stream, (const uintx4 *)X, idx, (uintx4 *)Xp, p->n, ilog2(cpr));
+    return launch_status();
+}
+
+extern "C" pbs_status pbs_unpermute(const pbs_problem *p, const void *Op, const int32_t *qidx, void *O, void *stream)
+{
+    pbs_status st = validate(p);
+    if (st != PBS_OK) return st;
+    if (!Op || !O) return PBS_ERR_NULL;
+    if (!aligned16(Op) || !aligned16(O)) return PBS_ERR_SHAPE;
+    if (Op == O) return qidx ? PBS_ERR_SHAPE : PBS_OK;     // in place only for the identity
+    const int cpr = (int)(p->d * elem_size(p->dtype) / 16);
+    hipLaunchKernelGGL(move_rows_kernel<true>, move_grid(p->n, cpr, p->batch * p->h_q), dim3(256), 0,
+                       (hipStream_t)stream, (const uintx4 *)Op, qidx, (uintx4 *)O, p->n, ilog2(cpr));
+    return launch_status();
+}

@@ -1,0 +1,57 @@
+"""Helpers for the GPU parity tests: host<->device marshalling and layout conversions (data movement only)."""
+import numpy as np
+import torch
+
+from paper_2510_21270_amd import binding as pbs
+from paper_2510_21270_amd import workloads as wl
+
+TOL = {"bf16": dict(max_abs=2e-2, mean_abs=2e-3), "f32": dict(max_abs=1e-4, mean_abs=1e-4)}
+
+
+def to_dev(x_f32, dtype):
+    """float32 numpy array with storage-exact values -> device tensor of the storage dtype."""
+    x = np.ascontiguousarray(x_f32, dtype=np.float32)
+    if dtype == "bf16":
+        bits = torch.from_numpy(wl.bf16_bits(x).view(np.int16))
+        return bits.view(torch.bfloat16).cuda()
+    return torch.from_numpy(x).cuda()
+
+
+def to_host(t):
+    """device tensor -> float64 numpy (bf16 widened exactly)."""
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+def i32_dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).cuda()
+
+
+def vt_layout(Vp, block):
+    """[B,H,N,d] (numpy) -> the library's block-transposed V' layout [B,H,T,d,block], zero padded."""
+    B, H, N, d = Vp.shape
+    T = -(-N // block)
+    pad = np.zeros((B, H, T * block, d), dtype=Vp.dtype)
+    pad[:, :, :N] = Vp
+    return np.ascontiguousarray(pad.reshape(B, H, T, block, d).transpose(0, 1, 2, 4, 3))
+
+
+def mask_from_bits(bits, T):
+    """int64 device tensor [B,Hq,T,W] -> uint8 numpy [B,Hq,T,T]."""
+    words = bits.cpu().numpy().view(np.uint64)
+    shifts = np.arange(64, dtype=np.uint64)
+    m = ((words[..., None] >> shifts) & np.uint64(1)).astype(np.uint8)
+    return m.reshape(words.shape[:-1] + (-1,))[..., :T]
+
+
+def make_problem(w, tau=None, flags=None, segment=None):
+    return pbs.problem(w.batch, w.h_q, w.h_kv, w.n, w.d, w.block, segment or w.segment, w.dtype,
+                       tau=w.tau if tau is None else tau, scale=0.0, flags=w.flags if flags is None else flags)
+
+
+def check_close(got, want, dtype, what=""):
+    err = np.abs(got - want)
+    tol = TOL[dtype]
+    assert np.isfinite(got).all(), what
+    assert err.max() <= tol["max_abs"], "%s max-abs %.3e > %.1e" % (what, err.max(), tol["max_abs"])
+    assert err.mean() <= tol["mean_abs"], "%s mean-abs %.3e > %.1e" % (what, err.mean(), tol["mean_abs"])
+    return float(err.max()), float(err.mean())

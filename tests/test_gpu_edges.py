@@ -1,0 +1,154 @@
+"""GPU parity on the degenerate and edge cases of the path (through the C ABI, against the oracle)."""
+import numpy as np
+import pytest
+import torch
+
+from gpu_helpers import check_close, i32_dev, make_problem, mask_from_bits, to_dev, to_host, vt_layout
+from paper_2510_21270_amd import binding as pbs
+from paper_2510_21270_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+def _full_pipeline_vs_oracle(oracle, w, tau=None, flags=None, exact_indices=True):
+    p = make_problem(w, tau=tau, flags=flags)
+    res = oracle.pipeline(w.Q, w.K, w.V, w.block, w.segment, p.tau, flags=p.flags)
+    pipe = pbs.Pipeline(p)
+    O = pipe.run(to_dev(w.Q, w.dtype), to_dev(w.K, w.dtype), to_dev(w.V, w.dtype))
+    torch.cuda.synchronize()
+    if exact_indices:
+        np.testing.assert_array_equal(pipe.kidx.cpu().numpy(), res["kidx"])
+        np.testing.assert_array_equal(mask_from_bits(pipe.mask_bits, w.T), res["mask"])
+        check_close(to_host(O), res["O"], w.dtype, w.name)
+    return pipe, res, O
+
+
+@pytest.mark.parametrize("n", [1, 5, 63, 64, 65])
+def test_tiny_lengths_f32(oracle, n):
+    # shorter than one block / one segment: no permutation at all, partial blocks everywhere
+    w = wl.planted("tiny%d" % n, 30 + n, 2, 1, n, 64, 64, 128, 0.9, "f32", 1)
+    _full_pipeline_vs_oracle(oracle, w)
+
+
+@pytest.mark.parametrize("n", [1, 100, 129])
+def test_tiny_lengths_bf16_mfma(oracle, n):
+    w = wl.planted("tinyb%d" % n, 40 + n, 2, 2, n, 128, 128, 128, 0.9, "bf16", 1)
+    pipe, res, O = _full_pipeline_vs_oracle(oracle, w, exact_indices=False)
+    # with at most two blocks everything allowed is forced, so the result is dense causal attention
+    check_close(to_host(O), oracle.dense_causal(w.Q, w.K, w.V), "bf16", "tiny bf16")
+
+
+@pytest.mark.parametrize("dtype,d,block,seg", [("f32", 64, 64, 256), ("bf16", 128, 128, 512), ("bf16", 128, 64, 256)])
+def test_tau_above_one_is_dense_causal(oracle, dtype, d, block, seg):
+    # every allowed block is kept, so the GPU pipeline must reproduce dense causal attention (Theorem 1),
+    # whatever order its scores put the keys in.
+    w = wl.planted("dense", 50, 4, 2, 1500, d, block, seg, 1.5, dtype, 8, rope_base=5e5)
+    p = make_problem(w)
+    pipe = pbs.Pipeline(p)
+    O = pipe.run(to_dev(w.Q, dtype), to_dev(w.K, dtype), to_dev(w.V, dtype))
+    torch.cuda.synchronize()
+    check_close(to_host(O), oracle.dense_causal(w.Q, w.K, w.V), dtype, "dense")
+    T, R, G = w.T, seg // block, 1500 // seg
+    want_cnt = np.array([min((i // R + 1) * R, T) if i // R < G else i + 1 for i in range(T)])
+    assert (pipe.row_cnt.cpu().numpy() == want_cnt).all()
+
+
+def test_tau_zero_keeps_one_block_plus_forced(oracle):
+    w = wl.planted("tau0", 51, 2, 1, 2048, 64, 64, 256, 0.0, "f32", 8)
+    pipe, res, O = _full_pipeline_vs_oracle(oracle, w, tau=0.0, flags=0)
+    R = 4
+    cnt = pipe.row_cnt.cpu().numpy()
+    assert cnt.max() <= R + 1
+
+
+def test_identity_permutation_when_scores_are_null(oracle):
+    # the unpermuted MeanPooling baseline: K' = K, V' = V
+    w = wl.planted("ident", 52, 2, 2, 777, 128, 128, 256, 0.9, "bf16", 4)
+    p = make_problem(w)
+    kidx, Kp, Vt = pbs.segment_permute(p, None, to_dev(w.K, "bf16"), to_dev(w.V, "bf16"))
+    torch.cuda.synchronize()
+    assert (kidx.cpu().numpy() == np.arange(777)).all()
+    np.testing.assert_array_equal(to_host(Kp), w.K.astype(np.float64))
+    np.testing.assert_array_equal(to_host(Vt), vt_layout(w.V, 128).astype(np.float64))
+
+
+def test_ties_and_signed_zero_scores(oracle):
+    n, seg = 1024, 256
+    p = pbs.problem(1, 1, 1, n, 64, 64, seg, "f32")
+    rng = np.random.default_rng(3)
+    s = rng.integers(0, 4, size=(1, 1, n)).astype(np.float32) * 0.25      # many exact ties
+    s[0, 0, ::5] = -0.0                                                   # -0.0 ties with +0.0
+    s[0, 0, 1::5] = 0.0
+    want = oracle.segment_argsort(s, seg)
+    kidx, _, _ = pbs.segment_permute(p, torch.from_numpy(s).cuda(), None, None, indices_only=True)
+    np.testing.assert_array_equal(kidx.cpu().numpy(), want)
+    s2 = np.zeros((1, 1, n), dtype=np.float32)                            # all equal -> identity
+    kidx, _, _ = pbs.segment_permute(p, torch.from_numpy(s2).cuda(), None, None, indices_only=True)
+    assert (kidx.cpu().numpy() == np.arange(n)).all()
+
+
+def test_maximum_segment_and_non_power_of_two_segment(oracle):
+    rng = np.random.default_rng(8)
+    for n, seg, block in [(4096 * 2 + 100, 4096, 128), (384 * 3 + 7, 384, 128), (96 * 5, 96, 32)]:
+        p = pbs.problem(1, 2, 2, n, 64, block, seg, "f32")
+        s = rng.random((1, 2, n)).astype(np.float32)
+        kidx, _, _ = pbs.segment_permute(p, torch.from_numpy(s).cuda(), None, None, indices_only=True)
+        np.testing.assert_array_equal(kidx.cpu().numpy(), oracle.segment_argsort(s, seg))
+
+
+@pytest.mark.parametrize("dtype,d,block", [("bf16", 128, 128), ("f32", 64, 32)])
+def test_given_lists_any_order_empty_rows_and_out_of_range_entries(oracle, dtype, d, block):
+    # config-5 style: identity key order, caller-supplied block lists
+    T, Hq, Hkv = 12, 4, 2
+    n = T * block - 9
+    rng = np.random.default_rng(21)
+    Q = rng.standard_normal((1, Hq, n, d)).astype(np.float32)
+    K = rng.standard_normal((1, Hkv, n, d)).astype(np.float32)
+    V = rng.standard_normal((1, Hkv, n, d)).astype(np.float32)
+    if dtype == "bf16":
+        Q, K, V = wl.round_to_bf16(Q), wl.round_to_bf16(K), wl.round_to_bf16(V)
+    row_cnt, col_idx = wl.random_block_lists(5, 1, Hq, T, 0.4)
+    kidx = np.tile(np.arange(n, dtype=np.int32), (1, Hkv, 1))
+    p = pbs.problem(1, Hq, Hkv, n, d, block, block, dtype)              # segment = block: plain block causality
+    want, want_lse = oracle.attn_fwd(Q, K, V, None, kidx, row_cnt, col_idx, block, want_lse=True)
+    # the same lists reversed, plus junk entries that the kernel must ignore (beyond the causal region / negative)
+    shuffled = col_idx.copy()
+    cnt2 = row_cnt.copy()
+    for h in range(Hq):
+        for i in range(T):
+            c = row_cnt[0, h, i]
+            lst = col_idx[0, h, i, :c][::-1].tolist()
+            if c + 2 <= T:
+                lst = [-1] + lst + [T + 3 if i == T - 1 else min(T - 1, i + 1)]
+                if lst[-1] <= i:
+                    lst = lst[:-1]
+            shuffled[0, h, i, :len(lst)] = lst
+            cnt2[0, h, i] = len(lst)
+    # one query block with an empty list: zero output rows and lse = -inf
+    cnt2[0, 1, 3] = 0
+    got, lse = pbs.attn_fwd(p, to_dev(Q, dtype), to_dev(K, dtype), to_dev(vt_layout(V, block), dtype), None,
+                            i32_dev(kidx), i32_dev(cnt2), i32_dev(shuffled), want_lse=True)
+    torch.cuda.synchronize()
+    got, lse = to_host(got), lse.cpu().numpy()
+    sl = slice(3 * block, 4 * block)
+    assert (got[0, 1, sl] == 0).all() and np.isneginf(lse[0, 1, sl]).all()
+    got[0, 1, sl] = want[0, 1, sl]
+    check_close(got, want, dtype, "given lists")
+    lse[0, 1, sl] = want_lse[0, 1, sl]
+    np.testing.assert_allclose(lse, want_lse, atol=2e-2 if dtype == "bf16" else 1e-4, rtol=0)
+
+
+def test_reversed_keys_rows_see_nothing_in_early_blocks(oracle):
+    # keys reversed inside one segment: early visited blocks are fully masked for early queries (running max -inf)
+    n, block, d = 512, 128, 128
+    rng = np.random.default_rng(6)
+    Q, K, V = (wl.round_to_bf16(rng.standard_normal((1, 1, n, d)).astype(np.float32)) for _ in range(3))
+    kidx = np.arange(n - 1, -1, -1, dtype=np.int32).reshape(1, 1, n)
+    Kp, Vp = oracle.gather_rows(K, kidx), oracle.gather_rows(V, kidx)
+    row_cnt = np.full((1, 1, 4), 4, dtype=np.int32)
+    col_idx = np.tile(np.arange(4, dtype=np.int32), (1, 1, 4, 1))
+    p = pbs.problem(1, 1, 1, n, d, block, n, "bf16")
+    got = pbs.attn_fwd(p, to_dev(Q, "bf16"), to_dev(Kp, "bf16"), to_dev(vt_layout(Vp, block), "bf16"), None,
+                       i32_dev(kidx), i32_dev(row_cnt), i32_dev(col_idx))
+    torch.cuda.synchronize()
+    check_close(to_host(got), oracle.dense_causal(Q, K, V), "bf16", "reversed")
