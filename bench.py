@@ -1,0 +1,200 @@
+#!/usr/bin/env python3
+"""Benchmark of the PBS-Attn prefill hot path on one MI355X.
+
+One "step" is one pass of the whole path (key scores -> segmented permutation -> block mask -> block-sparse
+attention -> inverse permutation) over one synthetic layer input that is already resident in HBM.  The default
+workload is the headline configuration: a Llama-3.1-8B-shaped layer (32 query heads, 8 kv heads, d=128, bf16) at
+N=131072, block 128, segment 1024, tau 0.9.
+
+Prints ONE JSON line.  `value` is the effective TFLOP/s of the whole step, counted over the blocks the attention
+kernel actually visits (4 * block^2 * d FLOP per block per query head).  `roofline` covers the dominant kernel
+(pbs_attn_fwd) from HIP-event timings taken inside the timed region; `cpu_baseline` is the fp64 oracle's attention
+loop timed on the host cores on a bounded sample of query blocks.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0       # MI355X dense bf16 matrix peak
+HBM_PEAK_GBS = 8000.0                # MI355X HBM3E
+
+
+def make_workload(name):
+    from paper_2510_21270_amd import workloads as wl
+    if name == "c3":
+        return wl.c3_llama128k()
+    if name == "c2":
+        return wl.c2_llama()
+    if name == "c4":
+        return wl.c4_qwen()
+    if name == "c1":
+        return wl.c1_tiny()
+    if name.startswith("c5"):
+        return wl.c5_density(float(name.split(":")[1]) if ":" in name else 0.25)
+    if name == "small":                                  # quick functional check of the script itself
+        return wl.c2_llama(n=8192, h_q=8, h_kv=2)
+    raise SystemExit("unknown workload %r" % name)
+
+
+def to_dev(x, dtype):
+    import numpy as np
+    import torch
+    from paper_2510_21270_amd import workloads as wl
+    if dtype == "bf16":
+        return torch.from_numpy(wl.bf16_bits(x).view(np.int16)).view(torch.bfloat16).cuda()
+    return torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).cuda()
+
+
+def cpu_baseline(w, seconds_budget=25.0):
+    """The oracle's attention loop (Algorithm 1, fp64, plain C + OpenMP) on a sample of query blocks with every
+    allowed block listed and the identity key order; reported in the metric's unit (TFLOP/s over visited blocks)."""
+    import numpy as np
+    from oracle import pbs_oracle as oracle
+    threads = oracle.num_threads()
+    T, R, G = w.T, w.segment // w.block, w.n // w.segment
+    flop_per_block = 4.0 * w.block * w.block * w.d
+    # calibrate on one short row, then pick rows until the budget is filled
+    rng = np.random.default_rng(0)
+    kidx = np.tile(np.arange(w.n, dtype=np.int32), (w.batch, w.h_kv, 1))
+
+    # the oracle takes [B,Hq,T,T] lists; build them sparsely populated for the sampled rows only
+    def run(rows):
+        row_cnt = np.zeros((w.batch, w.h_q, T), dtype=np.int32)
+        col_idx = np.zeros((w.batch, w.h_q, T, T), dtype=np.int32)
+        blocks = 0
+        for (b, h, i) in rows:
+            g = i // R
+            ni = min((g + 1) * R, T) if g < G else i + 1
+            row_cnt[b, h, i] = ni
+            col_idx[b, h, i, :ni] = np.arange(ni)
+            blocks += ni
+        t0 = time.perf_counter()
+        oracle.attn_rows(w.Q, w.K, w.V, None, kidx, row_cnt, col_idx, w.block, rows)
+        return time.perf_counter() - t0, blocks
+
+    i_cal = min(T - 1, max(1, 2 * R - 1))
+    t_cal, b_cal = run([[0, 0, i_cal]])
+    per_block_core = t_cal / b_cal                               # seconds per block on one core
+    budget_blocks = seconds_budget * threads / per_block_core
+    rows, total = [], 0
+    while total < budget_blocks and len(rows) < 4 * threads:
+        i = int(rng.integers(T // 2, T))
+        g = i // R
+        ni = min((g + 1) * R, T) if g < G else i + 1
+        rows.append([0, int(rng.integers(0, w.h_q)), i])
+        total += ni
+    secs, blocks = run(rows)
+    return {"value": blocks * flop_per_block / secs / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+            "sample": "%d query blocks (rows in the upper half, all allowed blocks listed, identity key order), "
+                      "%d blocks of %dx%dx%d, fp64, %.1f s wall" % (len(rows), blocks, w.block, w.block, w.d, secs)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="c3")
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        raise SystemExit("bench.py measures one GPU: the path shards by kv-head group with no exchange, and this "
+                         "build runs on one MI355X only (--gpus 1)")
+    import numpy as np
+    import torch
+    from paper_2510_21270_amd import binding as pbs
+
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    pbs.load_library()
+    t_gen = time.perf_counter()
+    w = make_workload(args.workload)
+    t_gen = time.perf_counter() - t_gen
+    p = pbs.problem(w.batch, w.h_q, w.h_kv, w.n, w.d, w.block, w.segment, w.dtype, tau=w.tau, flags=w.flags)
+    Q, K, V = to_dev(w.Q, w.dtype), to_dev(w.K, w.dtype), to_dev(w.V, w.dtype)
+    pipe = pbs.Pipeline(p)
+    given = "row_cnt" in w.extra                      # config 5: caller-supplied block lists, identity key order
+    if given:
+        row_cnt = torch.from_numpy(w.extra["row_cnt"]).cuda()
+        col_idx = torch.from_numpy(w.extra["col_idx"]).cuda()
+
+    names = ["key_scores", "segment_permute", "block_mask", "attn_fwd", "unpermute"]
+
+    def step(events=None):
+        def mark(k):
+            if events is not None:
+                events[k].record()
+        mark(0)
+        if given:
+            mark(1)
+            pbs.segment_permute(p, None, K, V, pipe.kidx, pipe.Kp, pipe.Vt)
+            mark(2)
+            mark(3)
+            pbs.attn_fwd(p, Q, pipe.Kp, pipe.Vt, None, pipe.kidx, row_cnt, col_idx, pipe.Op)
+        else:
+            pbs.key_scores(p, Q, K, pipe.scores, pipe.ws1)
+            mark(1)
+            pbs.segment_permute(p, pipe.scores, K, V, pipe.kidx, pipe.Kp, pipe.Vt)
+            mark(2)
+            pbs.block_mask(p, Q, pipe.Kp, pipe.mask_bits, pipe.row_cnt, pipe.col_idx, pipe.ws3)
+            mark(3)
+            pbs.attn_fwd(p, Q, pipe.Kp, pipe.Vt, None, pipe.kidx, pipe.row_cnt, pipe.col_idx, pipe.Op)
+        mark(4)
+        pbs.unpermute(p, pipe.Op, None, pipe.O)        # P_sigma = I in the paper's main setting: nothing to move
+        mark(5)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(evs[k])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    stage_ms = {nm: float(np.mean([evs[k][s].elapsed_time(evs[k][s + 1]) for k in range(args.steps)]))
+                for s, nm in enumerate(names)}
+
+    cnt = (row_cnt if given else pipe.row_cnt).cpu().numpy().astype(np.int64)
+    visited = int(cnt.sum())
+    T = w.T
+    causal_total = w.batch * w.h_q * T * (T + 1) // 2
+    flop = visited * 4.0 * w.block * w.block * w.d
+    es = 2 if w.dtype == "bf16" else 4
+    kv_bytes = 2 * w.batch * w.h_kv * w.n * w.d * es
+    q_bytes = w.batch * w.h_q * w.n * w.d * es
+    alg_bytes = {   # algorithmic HBM bytes of the bandwidth-bound stages (each tensor moved once)
+        "key_scores": kv_bytes // 2 + w.batch * w.h_q * min(w.block, w.n) * w.d * es + w.batch * w.h_kv * w.n * 4,
+        "segment_permute": 2 * kv_bytes + 2 * w.batch * w.h_kv * w.n * 4,
+        "block_mask": q_bytes + kv_bytes // 2 + visited * 4 + w.batch * w.h_q * T * ((T + 63) // 64) * 8,
+    }
+    if given:
+        alg_bytes = {"segment_permute": alg_bytes["segment_permute"] - w.batch * w.h_kv * w.n * 4}
+    attn_tflops = flop / (stage_ms["attn_fwd"] * 1e-3) / 1e12
+    out = {
+        "metric": "pbs_attn_prefill_effective_tflops", "value": flop / (ms_per_step * 1e-3) / 1e12, "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "ms_per_layer": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": dict(w.describe(), visited_blocks=visited, causal_blocks=causal_total,
+                       density_vs_causal=visited / causal_total, given_mask=bool(given)),
+        "stages_ms": stage_ms,
+        "stages_gbs": {k: alg_bytes[k] / (stage_ms[k] * 1e-3) / 1e9 for k in alg_bytes if stage_ms[k] > 0},
+        "roofline": {"kernel": "pbs_attn_fwd", "bound": "mfma", "achieved": attn_tflops,
+                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": attn_tflops / MFMA_BF16_PEAK_TFLOPS,
+                     "traffic": None, "avg_launch_ms": stage_ms["attn_fwd"]},
+        "context": {"paper_h100_128k_ms": {"flashattention": 443.29, "pbs_total": 159.87, "speedup": 2.77},
+                    "input_generation_s": t_gen},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

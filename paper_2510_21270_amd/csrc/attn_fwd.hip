@@ -26,25 +26,183 @@ __device__ inline int swap23(int m) { return (m & ~12) | ((m & 4) << 1) | ((m & 
 
 // ---------------------------------------------------------------------------------------------
 // MFMA kernel.  BLOCK = block size; WAVES = waves per workgroup; each wave owns BLOCK / WAVES query rows.
+// Key blocks are consumed in sub-tiles of KT = 64 keys.  K' and V'^T sub-tiles are double-buffered in LDS and
+// filled by asynchronous global->LDS loads (no registers, no LDS store instructions): while sub-tile s is being
+// multiplied, sub-tile s+1 is in flight.  One barrier per sub-tile.
 // grid = (T, batch*h_q); blockIdx.x = T-1-i so that the long rows are dispatched first.
 // ---------------------------------------------------------------------------------------------
+constexpr int KT = 64;                                     // keys per sub-tile
+constexpr int kListChunk = 1024;                           // listed blocks staged in LDS at a time
+
+typedef const __attribute__((address_space(1))) void *gptr_t;
+typedef __attribute__((address_space(3))) void *lptr_t;
+
+// Issue this wave's share of the loads of one sub-tile.  One instruction moves 64 lanes x 16 bytes into 1 KiB of
+// contiguous LDS; which global chunk a lane fetches is chosen so that the LDS image is the swizzled tile:
+//   K' sub-tile  [KT rows][128 d]  (256-byte rows): LDS row r holds key (r & ~31) | swap23(r & 31),
+//                                                   16-byte chunk c of that key sits at chunk c ^ (r & 15);
+//   V'^T sub-tile [128 rows][KT keys] (128-byte rows): chunk c of row r sits at chunk c ^ ((r >> 1) & 7).
 template <int BLOCK, int WAVES>
-__global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(
+__device__ inline void issue_subtile(bf16_t *kbuf, bf16_t *vbuf, int *kpos, const bf16_t *Kh, const bf16_t *Vh,
+                                     const int32_t *kih, int j, int half, int n, bool masked, int wave, int lane)
+{
+    constexpr int D = 128;
+    constexpr int KI = KT * D * 2 / 1024;                 // 16 instructions for K'
+    constexpr int VI = D * KT * 2 / 1024;                 // 16 instructions for V'^T
+#pragma unroll
+    for (int x = wave; x < KI; x += WAVES) {
+        const int r = 4 * x + (lane >> 4);
+        const int pc = lane & 15;
+        const int key = (r & ~31) | swap23(r & 31);
+        int slot = j * BLOCK + half * KT + key;
+        if (slot >= n) slot = n - 1;                      // clamped; such keys are masked before the softmax
+        const bf16_t *src = Kh + (size_t)slot * D + ((pc ^ (r & 15)) << 3);
+        __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(kbuf + x * 512), 16, 0, 0);
+    }
+#pragma unroll
+    for (int x = wave; x < VI; x += WAVES) {
+        const int r = 8 * x + (lane >> 3);
+        const int pc = lane & 7;
+        const bf16_t *src = Vh + ((size_t)j * D + r) * BLOCK + half * KT + ((pc ^ ((r >> 1) & 7)) << 3);
+        __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(vbuf + x * 512), 16, 0, 0);
+    }
+    if (masked && wave == WAVES - 1) {                    // original positions of the sub-tile's 64 keys
+        int slot = j * BLOCK + half * KT + lane;
+        if (slot >= n) slot = n - 1;                      // clamped; slots >= n are rejected by index below
+        __builtin_amdgcn_global_load_lds((gptr_t)(kih + slot), (lptr_t)kpos, 4, 0, 0);
+    }
+}
+
+// Barrier that also publishes the asynchronous global->LDS loads of every wave: the loads of a wave are only
+// counted by that wave's own vmcnt, and the workgroup-scope fence of __syncthreads() does not wait on them, so
+// each wave drains its own counter (s_waitcnt vmcnt(0), gfx9 encoding) before it arrives at the barrier.
+__device__ inline void sync_tiles()
+{
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    __syncthreads();
+}
+
+template <int NT>
+struct AttnState {
+    floatx16 acc_o[4][NT];
+    float m2[NT], l[NT];
+};
+
+// One sub-tile: S^T = K' Q'^T, causal mask if needed, online softmax, O^T += V'^T P^T.
+template <int BLOCK, int NT>
+__device__ inline void compute_subtile(AttnState<NT> &st, const bf16_t *kbuf, const bf16_t *vbuf,
+                                       const bf16x8 (&qf)[NT][8], const int (&qpos)[NT], const int *kpos, int j,
+                                       int half, int n, bool masked, float c2, int ln, int lh)
+{
+    constexpr int D = 128;
+    floatx16 acc_s[2][NT];
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int x = 0; x < 16; ++x) acc_s[mt][nt][x] = 0.0f;
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt) {
+        const int lrow = 32 * mt + ln;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const bf16x8 a = *reinterpret_cast<const bf16x8 *>(kbuf + lrow * D + (((2 * k + lh) ^ (lrow & 15)) << 3));
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+                acc_s[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[nt][k], acc_s[mt][nt], 0, 0, 0);
+        }
+    }
+    // acc_s[mt][nt][x]: key (within the sub-tile) = 32 mt + 16 (x / 8) + 8 h + (x % 8), query = q0 + 32 nt + n
+    if (masked) {
+        const int room = n - (j * BLOCK + half * KT);     // key slots of this sub-tile that exist
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int k8 = 32 * mt + 16 * u + 8 * lh;  // 8 consecutive keys of this lane
+                const int4 a = *reinterpret_cast<const int4 *>(kpos + k8);
+                const int4 b = *reinterpret_cast<const int4 *>(kpos + k8 + 4);
+                const int kp[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+#pragma unroll
+                for (int x = 0; x < 8; ++x)
+#pragma unroll
+                    for (int nt = 0; nt < NT; ++nt)
+                        if (kp[x] > qpos[nt] || k8 + x >= room) acc_s[mt][nt][8 * u + x] = -INFINITY;
+            }
+    }
+    // online softmax in the log2 domain; P is packed to bf16 straight into the second product's B operand
+    bf16x8 pf[NT][4];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        float rmax = -INFINITY;
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int x = 0; x < 16; ++x) rmax = fmaxf(rmax, acc_s[mt][nt][x]);
+        rmax = fmaxf(rmax, __shfl_xor(rmax, 32, 64));
+        const float mnew = fmaxf(st.m2[nt], rmax * c2);
+        const float muse = mnew == -INFINITY ? 0.0f : mnew;
+        const float alpha = __builtin_amdgcn_exp2f(st.m2[nt] - muse);
+        float rsum = 0.0f;
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                floatx2 pr[4];
+#pragma unroll
+                for (int x = 0; x < 8; ++x) {
+                    const float p = __builtin_amdgcn_exp2f(acc_s[mt][nt][8 * u + x] * c2 - muse);
+                    rsum += p;
+                    pr[x >> 1][x & 1] = p;
+                }
+                bf16x8 pk;
+#pragma unroll
+                for (int y = 0; y < 4; ++y) {
+                    const bf16x2 t2 = __builtin_convertvector(pr[y], bf16x2);
+                    pk[2 * y] = t2[0];
+                    pk[2 * y + 1] = t2[1];
+                }
+                pf[nt][2 * mt + u] = pk;
+            }
+        st.l[nt] = st.l[nt] * alpha + rsum;
+        st.m2[nt] = mnew;
+        if (__any(alpha != 1.0f)) {                        // the running maximum moved for some query of the wave
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+                for (int x = 0; x < 16; ++x) st.acc_o[dt][nt][x] *= alpha;
+        }
+    }
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) {
+        const int row = 32 * dt + ln;
+        const int sw = (row >> 1) & 7;
+#pragma unroll
+        for (int k2 = 0; k2 < 4; ++k2) {
+            const bf16x8 a = *reinterpret_cast<const bf16x8 *>(vbuf + row * KT + (((2 * k2 + lh) ^ sw) << 3));
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+                st.acc_o[dt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[nt][k2], st.acc_o[dt][nt], 0, 0, 0);
+        }
+    }
+}
+
+template <int BLOCK, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVES / 2, WAVES / 2))) void attn_mfma_kernel(
     const bf16_t *__restrict__ Qp, const bf16_t *__restrict__ Kp, const bf16_t *__restrict__ Vt,
     const int32_t *__restrict__ qidx, const int32_t *__restrict__ kidx, const int32_t *__restrict__ row_cnt,
     const int32_t *__restrict__ col_idx, bf16_t *__restrict__ Op, float *__restrict__ lse, Geo g)
 {
     constexpr int D = 128;
-    constexpr int THREADS = WAVES * 64;
     constexpr int NT = BLOCK / WAVES / 32;         // 32-query tiles per wave
-    constexpr int MT = BLOCK / 32;                 // 32-key tiles per block
-    constexpr int KS2 = BLOCK / 16;                // 16-key contraction steps of the second product
-    constexpr int VCH = BLOCK / 8;                 // 16-byte chunks per V'^T row
-    static_assert(NT >= 1, "each wave needs at least one 32-query tile");
+    constexpr int SUBS = BLOCK / KT;               // sub-tiles per key block
+    static_assert(NT >= 1 && SUBS >= 1, "unsupported tiling");
 
-    __shared__ __align__(16) bf16_t ks[BLOCK * D];   // K' tile, row = swap23(key), chunk ^= row & 15
-    __shared__ __align__(16) bf16_t vs[D * BLOCK];   // V'^T tile, row = d index, swizzled chunks
-    __shared__ int kpos[BLOCK];                      // original positions of the tile's keys
+    __shared__ __align__(16) bf16_t kbuf0[KT * D], kbuf1[KT * D];   // 16 KiB each
+    __shared__ __align__(16) bf16_t vbuf0[D * KT], vbuf1[D * KT];   // 16 KiB each
+    __shared__ __align__(16) int kpos0[KT], kpos1[KT];
+    __shared__ int jl[kListChunk];                                   // validated block list, -1 = skip
 
     const int i = g.T - 1 - (int)blockIdx.x;
     const int bhq = blockIdx.y;
@@ -67,16 +225,15 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(
         qpos[nt] = qs < g.n ? (qidx ? qidx[(size_t)bhq * g.n + qs] : qs) : -1;
     }
 
-    floatx16 acc_o[4][NT];
-    float m2[NT], l[NT];
+    AttnState<NT> st;
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
-        m2[nt] = -INFINITY;
-        l[nt] = 0.0f;
+        st.m2[nt] = -INFINITY;
+        st.l[nt] = 0.0f;
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-            for (int x = 0; x < 16; ++x) acc_o[dt][nt][x] = 0.0f;
+            for (int x = 0; x < 16; ++x) st.acc_o[dt][nt][x] = 0.0f;
     }
 
     const float c2 = g.scale * kLog2eF;
@@ -88,121 +245,51 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(
     const bf16_t *Vh = Vt + bhk * (size_t)g.T * D * BLOCK;
     const int32_t *kih = kidx + bhk * (size_t)g.n;
 
-    for (int t = 0; t < cnt; ++t) {
-        const int j = cols[t];
-        if (j < 0 || j >= ni) continue;                       // uniform across the workgroup
-        const bool masked = j >= jmask;
-        __syncthreads();                                      // previous tile fully consumed
-        // ---- stage K' tile (BLOCK rows x 16 chunks) and V'^T tile (128 rows x VCH chunks)
-        for (int c = threadIdx.x; c < BLOCK * 16; c += THREADS) {
-            const int row = c >> 4, ch = c & 15;
-            int slot = j * BLOCK + row;
-            if (slot >= g.n) slot = g.n - 1;                  // clamped; such keys are masked below
-            const uintx4 v = *reinterpret_cast<const uintx4 *>(Kh + (size_t)slot * D + ch * 8);
-            const int lrow = (row & ~31) | swap23(row & 31);
-            *reinterpret_cast<uintx4 *>(ks + lrow * D + ((ch ^ (lrow & 15)) << 3)) = v;
+    // The list is consumed in chunks staged in LDS (read back with LDS loads, which do not wait on the
+    // asynchronous tile loads).  Entries outside the columns the causal mask admits become -1 and are skipped;
+    // every test on them is uniform across the workgroup.  Sub-tile s of a chunk covers half (s % SUBS) of listed
+    // block jl[s / SUBS].
+    for (int base = 0; base < cnt; base += kListChunk) {
+        const int len = min(kListChunk, cnt - base);
+        __syncthreads();                   // previous chunk fully consumed
+        for (int t = threadIdx.x; t < len; t += WAVES * 64) {
+            const int j = cols[base + t];
+            jl[t] = (j >= 0 && j < ni) ? j : -1;
         }
-        for (int c = threadIdx.x; c < D * VCH; c += THREADS) {
-            const int row = c / VCH, ch = c % VCH;
-            const uintx4 v = *reinterpret_cast<const uintx4 *>(Vh + ((size_t)j * D + row) * BLOCK + ch * 8);
-            const int sw = BLOCK == 128 ? (row & 15) : ((row >> 1) & 7);
-            *reinterpret_cast<uintx4 *>(vs + row * BLOCK + ((ch ^ sw) << 3)) = v;
-        }
-        if (masked)
-            for (int c = threadIdx.x; c < BLOCK; c += THREADS) {
-                const int slot = j * BLOCK + c;
-                kpos[c] = slot < g.n ? kih[slot] : INT_MAX;
-            }
         __syncthreads();
-
-        // ---- S^T = K' Q'^T
-        floatx16 acc_s[MT][NT];
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-                for (int x = 0; x < 16; ++x) acc_s[mt][nt][x] = 0.0f;
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            const int lrow = 32 * mt + ln;
-#pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                const bf16x8 a =
-                    *reinterpret_cast<const bf16x8 *>(ks + lrow * D + (((2 * k + lh) ^ (lrow & 15)) << 3));
-#pragma unroll
-                for (int nt = 0; nt < NT; ++nt)
-                    acc_s[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[nt][k], acc_s[mt][nt], 0, 0, 0);
+        const int total = len * SUBS;
+        {
+            const int j0 = jl[0];
+            if (j0 >= 0)
+                issue_subtile<BLOCK, WAVES>(kbuf0, vbuf0, kpos0, Kh, Vh, kih, j0, 0, g.n, j0 >= jmask, wave, lane);
+        }
+        for (int s = 0; s < total; s += 2) {
+            sync_tiles();                  // sub-tile s has landed in buffer 0; buffer 1 is free again
+            if (s + 1 < total) {
+                const int j1 = jl[(s + 1) / SUBS];
+                if (j1 >= 0)
+                    issue_subtile<BLOCK, WAVES>(kbuf1, vbuf1, kpos1, Kh, Vh, kih, j1, (s + 1) % SUBS, g.n, j1 >= jmask,
+                                                wave, lane);
             }
-        }
-        // acc_s[mt][nt][x]: key (within the block) = 32 mt + 16 (x / 8) + 8 h + (x % 8), query = q0 + 32 nt + n
-
-        // ---- token-level causality inside the query block's own segment / the unpermuted tail
-        if (masked) {
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                for (int x = 0; x < 16; ++x) {
-                    const int kp = kpos[32 * mt + 16 * (x >> 3) + 8 * lh + (x & 7)];
-#pragma unroll
-                    for (int nt = 0; nt < NT; ++nt)
-                        if (kp > qpos[nt]) acc_s[mt][nt][x] = -INFINITY;
-                }
-        }
-
-        // ---- online softmax (log2 domain), P packed to bf16 in place of the second product's B operand
-        bf16x8 pf[NT][KS2];
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-            float rmax = -INFINITY;
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                for (int x = 0; x < 16; ++x) rmax = fmaxf(rmax, acc_s[mt][nt][x]);
-            rmax = fmaxf(rmax, __shfl_xor(rmax, 32, 64));
-            const float mnew = fmaxf(m2[nt], rmax * c2);
-            const float muse = mnew == -INFINITY ? 0.0f : mnew;
-            const float alpha = __builtin_amdgcn_exp2f(m2[nt] - muse);
-            float rsum = 0.0f;
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                for (int u = 0; u < 2; ++u) {
-                    floatx2 pr[4];
-#pragma unroll
-                    for (int x = 0; x < 8; ++x) {
-                        const float p = __builtin_amdgcn_exp2f(acc_s[mt][nt][8 * u + x] * c2 - muse);
-                        rsum += p;
-                        pr[x >> 1][x & 1] = p;
-                    }
-                    bf16x8 pk;
-#pragma unroll
-                    for (int y = 0; y < 4; ++y) {
-                        const bf16x2 t2 = __builtin_convertvector(pr[y], bf16x2);
-                        pk[2 * y] = t2[0];
-                        pk[2 * y + 1] = t2[1];
-                    }
-                    pf[nt][2 * mt + u] = pk;
-                }
-            l[nt] = l[nt] * alpha + rsum;
-            m2[nt] = mnew;
-#pragma unroll
-            for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-                for (int x = 0; x < 16; ++x) acc_o[dt][nt][x] *= alpha;
-        }
-
-        // ---- O^T += V'^T P^T
-#pragma unroll
-        for (int dt = 0; dt < 4; ++dt) {
-            const int row = 32 * dt + ln;
-            const int sw = BLOCK == 128 ? (row & 15) : ((row >> 1) & 7);
-#pragma unroll
-            for (int k2 = 0; k2 < KS2; ++k2) {
-                const bf16x8 a = *reinterpret_cast<const bf16x8 *>(vs + row * BLOCK + (((2 * k2 + lh) ^ sw) << 3));
-#pragma unroll
-                for (int nt = 0; nt < NT; ++nt)
-                    acc_o[dt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[nt][k2], acc_o[dt][nt], 0, 0, 0);
+            {
+                const int j = jl[s / SUBS];
+                if (j >= 0)
+                    compute_subtile<BLOCK, NT>(st, kbuf0, vbuf0, qf, qpos, kpos0, j, s % SUBS, g.n, j >= jmask, c2, ln,
+                                               lh);
+            }
+            if (s + 1 >= total) break;
+            sync_tiles();                  // sub-tile s+1 has landed in buffer 1; buffer 0 is free again
+            if (s + 2 < total) {
+                const int j2 = jl[(s + 2) / SUBS];
+                if (j2 >= 0)
+                    issue_subtile<BLOCK, WAVES>(kbuf0, vbuf0, kpos0, Kh, Vh, kih, j2, (s + 2) % SUBS, g.n, j2 >= jmask,
+                                                wave, lane);
+            }
+            {
+                const int j = jl[(s + 1) / SUBS];
+                if (j >= 0)
+                    compute_subtile<BLOCK, NT>(st, kbuf1, vbuf1, qf, qpos, kpos1, j, (s + 1) % SUBS, g.n, j >= jmask,
+                                               c2, ln, lh);
             }
         }
     }
@@ -210,7 +297,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(
     // ---- O' = diag(l)^-1 O; acc_o[dt][nt][x]: d = 32 dt + 8 (x / 4) + 4 h + (x % 4), query = q0 + 32 nt + n
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
-        const float lt = l[nt] + __shfl_xor(l[nt], 32, 64);
+        const float lt = st.l[nt] + __shfl_xor(st.l[nt], 32, 64);
         const float inv = lt > 0.0f ? 1.0f / lt : 0.0f;
         const int qs = q0 + 32 * nt + ln;
         if (qs < g.n) {
@@ -219,14 +306,14 @@ __global__ __launch_bounds__(WAVES * 64) void attn_mfma_kernel(
             for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
                 for (int gq = 0; gq < 4; ++gq) {
-                    floatx2 a = {acc_o[dt][nt][4 * gq] * inv, acc_o[dt][nt][4 * gq + 1] * inv};
-                    floatx2 bb = {acc_o[dt][nt][4 * gq + 2] * inv, acc_o[dt][nt][4 * gq + 3] * inv};
+                    floatx2 a = {st.acc_o[dt][nt][4 * gq] * inv, st.acc_o[dt][nt][4 * gq + 1] * inv};
+                    floatx2 bb = {st.acc_o[dt][nt][4 * gq + 2] * inv, st.acc_o[dt][nt][4 * gq + 3] * inv};
                     const bf16x2 pa = __builtin_convertvector(a, bf16x2), pb = __builtin_convertvector(bb, bf16x2);
                     bf16x4 o4 = {pa[0], pa[1], pb[0], pb[1]};
                     *reinterpret_cast<bf16x4 *>(dst + 32 * dt + 8 * gq + 4 * lh) = o4;
                 }
             if (lse && lh == 0)
-                lse[(size_t)bhq * g.n + qs] = lt > 0.0f ? (m2[nt] + log2f(lt)) * kLn2F : -INFINITY;
+                lse[(size_t)bhq * g.n + qs] = lt > 0.0f ? (st.m2[nt] + log2f(lt)) * kLn2F : -INFINITY;
         }
     }
 }
@@ -354,7 +441,7 @@ extern "C" pbs_status pbs_attn_fwd(const pbs_problem *p, const void *Qp, const v
     const dim3 grid(g.T, g.batch * g.h_q);
     if (p->dtype == PBS_BF16 && p->d == 128 && (p->block == 128 || p->block == 64)) {
         if (p->block == 128)
-            hipLaunchKernelGGL((attn_mfma_kernel<128, 2>), grid, dim3(128), 0, s, (const bf16_t *)Qp,
+            hipLaunchKernelGGL((attn_mfma_kernel<128, 4>), grid, dim3(256), 0, s, (const bf16_t *)Qp,
                                (const bf16_t *)Kp, (const bf16_t *)Vt, qidx, kidx, row_cnt, col_idx, (bf16_t *)Op, lse,
                                g);
         else
