@@ -29,10 +29,12 @@ __device__ inline int swap23(int m) { return (m & ~12) | ((m & 4) << 1) | ((m & 
 // Key blocks are consumed in sub-tiles of KT = 64 keys.  K' and V'^T sub-tiles are double-buffered in LDS and
 // filled by asynchronous global->LDS loads (no registers, no LDS store instructions): while sub-tile s is being
 // multiplied, sub-tile s+1 is in flight.  One barrier per sub-tile.
-// grid = (T, batch*h_q); blockIdx.x = T-1-i so that the long rows are dispatched first.
+// grid = 1-D, see the workgroup decoding at the top of the kernel (mfma_grid() on the host).
 // ---------------------------------------------------------------------------------------------
 constexpr int KT = 64;                                     // keys per sub-tile
 constexpr int kListChunk = 1024;                           // listed blocks staged in LDS at a time
+constexpr int kXcds = 8;                                   // accelerator dies, each with a private L2
+constexpr int kCohort = 64;                                // workgroups resident per XCD (32 CUs x 2)
 
 typedef const __attribute__((address_space(1))) void *gptr_t;
 typedef __attribute__((address_space(3))) void *lptr_t;
@@ -204,10 +206,24 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
     __shared__ __align__(16) int kpos0[KT], kpos1[KT];
     __shared__ int jl[kListChunk];                                   // validated block list, -1 = skip
 
-    const int i = g.T - 1 - (int)blockIdx.x;
-    const int bhq = blockIdx.y;
-    const int b = bhq / g.h_q, hq = bhq % g.h_q;
-    const size_t bhk = (size_t)b * g.h_kv + hq / g.r;
+    // Workgroup -> (query head, query block).  Workgroups are handed to the 8 XCDs round-robin by linear id and
+    // every XCD has its own L2, so the id is decoded as (xcd, slot): the 64 workgroups that are resident on one XCD
+    // at a time form a cohort of 64 rows of ONE kv head with nearly equal list lengths (16 consecutive query blocks
+    // x the r query heads of the group, longest first).  A cohort walks its ascending lists in near lock-step, so a
+    // K'/V' sub-tile is fetched into that L2 once and hit by the other members.
+    const int nbk = g.batch * g.h_kv;
+    const int rows_per_unit = g.r * g.T;
+    const int coh_per_unit = (rows_per_unit + kCohort - 1) / kCohort;
+    const int xcd = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
+    const int coh = (slot / kCohort) * kXcds + xcd;
+    if (coh >= nbk * coh_per_unit) return;
+    const int unit = coh % nbk;
+    const int mrow = (coh / nbk) * kCohort + slot % kCohort;
+    if (mrow >= rows_per_unit) return;
+    const int i = g.T - 1 - mrow / g.r;
+    const int b = unit / g.h_kv, hq = (unit % g.h_kv) * g.r + mrow % g.r;
+    const int bhq = b * g.h_q + hq;
+    const size_t bhk = unit;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int ln = lane & 31, lh = lane >> 5;
     const int q0 = i * BLOCK + wave * (BLOCK / WAVES);
@@ -438,14 +454,15 @@ extern "C" pbs_status pbs_attn_fwd(const pbs_problem *p, const void *Qp, const v
     if (!aligned16(Qp) || !aligned16(Kp) || !aligned16(Vt) || !aligned16(Op)) return PBS_ERR_SHAPE;
     const Geo g = make_geo(p);
     hipStream_t s = (hipStream_t)stream;
-    const dim3 grid(g.T, g.batch * g.h_q);
     if (p->dtype == PBS_BF16 && p->d == 128 && (p->block == 128 || p->block == 64)) {
+        const int ncoh = g.batch * g.h_kv * ((g.r * g.T + kCohort - 1) / kCohort);
+        const dim3 mgrid((unsigned)(((ncoh + kXcds - 1) / kXcds) * kCohort * kXcds));
         if (p->block == 128)
-            hipLaunchKernelGGL((attn_mfma_kernel<128, 4>), grid, dim3(256), 0, s, (const bf16_t *)Qp,
+            hipLaunchKernelGGL((attn_mfma_kernel<128, 4>), mgrid, dim3(256), 0, s, (const bf16_t *)Qp,
                                (const bf16_t *)Kp, (const bf16_t *)Vt, qidx, kidx, row_cnt, col_idx, (bf16_t *)Op, lse,
                                g);
         else
-            hipLaunchKernelGGL((attn_mfma_kernel<64, 2>), grid, dim3(128), 0, s, (const bf16_t *)Qp,
+            hipLaunchKernelGGL((attn_mfma_kernel<64, 2>), mgrid, dim3(128), 0, s, (const bf16_t *)Qp,
                                (const bf16_t *)Kp, (const bf16_t *)Vt, qidx, kidx, row_cnt, col_idx, (bf16_t *)Op, lse,
                                g);
         return launch_status();
