@@ -21,6 +21,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0       # MI355X dense bf16 matrix peak
+# HBM bytes per pbs_attn_fwd launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same counters
+# read for a plain 1 GiB copy (profiles/bench_c3_hbm_traffic.md); only known for the workloads listed here.
+ATTN_TRAFFIC_BYTES = {"c3": 17393300 * 2.0 * 1024 * (1048576 / 524346 / 2.0) + 1048580 * 1024.0}
 HBM_PEAK_GBS = 8000.0                # MI355X HBM3E
 
 
@@ -101,6 +104,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="c3")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="after the timed region, run one plain device copy of known size through pbs_unpermute, so "
+                         "that a rocprofv3 --pmc run of this command shows what FETCH_SIZE / WRITE_SIZE read for it")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py measures one GPU: the path shards by kv-head group with no exchange, and this "
@@ -160,6 +166,14 @@ def main():
     stage_ms = {nm: float(np.mean([evs[k][s].elapsed_time(evs[k][s + 1]) for k in range(args.steps)]))
                 for s, nm in enumerate(names)}
 
+    if args.copy_calibration:
+        scratch = torch.empty_like(pipe.Op)
+        pbs.unpermute(p, pipe.Op, None, scratch)           # identity sigma + distinct output = plain copy
+        torch.cuda.synchronize()
+        print("copy calibration: move_rows_kernel<true> read %d bytes and wrote %d bytes" %
+              (scratch.numel() * scratch.element_size(), scratch.numel() * scratch.element_size()), file=sys.stderr)
+        del scratch
+
     cnt = (row_cnt if given else pipe.row_cnt).cpu().numpy().astype(np.int64)
     visited = int(cnt.sum())
     T = w.T
@@ -187,7 +201,7 @@ def main():
         "stages_gbs": {k: alg_bytes[k] / (stage_ms[k] * 1e-3) / 1e9 for k in alg_bytes if stage_ms[k] > 0},
         "roofline": {"kernel": "pbs_attn_fwd", "bound": "mfma", "achieved": attn_tflops,
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": attn_tflops / MFMA_BF16_PEAK_TFLOPS,
-                     "traffic": None, "avg_launch_ms": stage_ms["attn_fwd"]},
+                     "traffic": ATTN_TRAFFIC_BYTES.get(args.workload), "avg_launch_ms": stage_ms["attn_fwd"]},
         "context": {"paper_h100_128k_ms": {"flashattention": 443.29, "pbs_total": 159.87, "speedup": 2.77},
                     "input_generation_s": t_gen},
     }

@@ -36,9 +36,10 @@ def load_library():
     """Load libpbs.so built in-tree (python -m paper_2510_21270_amd.build).  Fails loudly when it is missing."""
     global _lib
     if _lib is None:
-        if not os.path.exists(LIB_PATH):
-            raise PbsError("libpbs.so not found at %s: build it with `python -m paper_2510_21270_amd.build`" % LIB_PATH)
-        lib = ctypes.CDLL(LIB_PATH)
+        path = os.environ.get("PBS_LIBRARY", LIB_PATH)     # override for trying out another build of the library
+        if not os.path.exists(path):
+            raise PbsError("libpbs.so not found at %s: build it with `python -m paper_2510_21270_amd.build`" % path)
+        lib = ctypes.CDLL(path)
         P, V, Z = ctypes.POINTER(pbs_problem), ctypes.c_void_p, ctypes.c_size_t
         lib.pbs_status_string.restype = ctypes.c_char_p
         lib.pbs_status_string.argtypes = [ctypes.c_int]

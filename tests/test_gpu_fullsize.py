@@ -1,0 +1,94 @@
+"""GPU parity at the FULL sizes of configs 2 and 3 (Llama-3.1-8B-shaped layer, N = 32768 and N = 131072), in the
+launch configuration bench.py times (the same binding calls on the same preallocated Pipeline buffers).
+
+Discrete outputs (permutation indices, permuted tensors, block masks, block lists) are compared in full and must be
+bit-exact.  The attention output is compared on SAMPLED query blocks that the oracle computes one by one: first
+block, last block, blocks at segment edges and random ones, spread over the query heads.  Every stage is fed the
+oracle's previous stage, so each comparison isolates one stage.
+"""
+import numpy as np
+import pytest
+import torch
+
+from gpu_helpers import check_close, i32_dev, make_problem, mask_from_bits, to_dev, to_host, vt_layout
+from paper_2510_21270_amd import binding as pbs
+from paper_2510_21270_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+_state = {}
+
+
+def _setup(name, oracle):
+    """Generate the workload, run the oracle's stages 1-3 in full, upload, and keep everything for the tests."""
+    if name in _state:
+        return _state[name]
+    _state.clear()                                   # one full-size workload in memory at a time
+    torch.cuda.empty_cache()
+    w = wl.c2_llama() if name == "c2" else wl.c3_llama128k()
+    s = oracle.key_scores(w.Q, w.K, w.block)
+    s_h = s.astype(np.float32)
+    kidx = oracle.segment_argsort(s_h, w.segment)
+    Kp, Vp = oracle.gather_rows(w.K, kidx), oracle.gather_rows(w.V, kidx)
+    mask, row_cnt, col_idx = oracle.block_mask(w.Q, Kp, w.block, w.segment, w.tau, flags=w.flags)
+    p = make_problem(w)
+    st = dict(w=w, p=p, s=s, s_h=s_h, kidx=kidx, Kp=Kp, Vp=Vp, mask=mask, row_cnt=row_cnt, col_idx=col_idx,
+              Q=to_dev(w.Q, "bf16"), K=to_dev(w.K, "bf16"), V=to_dev(w.V, "bf16"), pipe=pbs.Pipeline(p))
+    _state[name] = st
+    return st
+
+
+@pytest.mark.parametrize("name", ["c2", "c3"])
+def test_full_size_scores_permutation_and_mask(oracle, name):
+    st = _setup(name, oracle)
+    w, p, pipe = st["w"], st["p"], st["pipe"]
+    # stage 1: by value
+    pbs.key_scores(p, st["Q"], st["K"], pipe.scores, pipe.ws1)
+    torch.cuda.synchronize()
+    got = pipe.scores.cpu().numpy().astype(np.float64)
+    np.testing.assert_allclose(got, st["s"], rtol=2e-3, atol=1e-37)
+    np.testing.assert_allclose(got.sum(-1), 1.0, rtol=1e-3)
+    # stage 2 on the oracle's scores: bit-exact indices and permuted tensors
+    pbs.segment_permute(p, torch.from_numpy(st["s_h"]).cuda(), st["K"], st["V"], pipe.kidx, pipe.Kp, pipe.Vt)
+    torch.cuda.synchronize()
+    assert np.array_equal(pipe.kidx.cpu().numpy(), st["kidx"])
+    assert torch.equal(pipe.Kp, to_dev(st["Kp"], "bf16"))
+    assert torch.equal(pipe.Vt, to_dev(vt_layout(st["Vp"], w.block), "bf16"))
+    # stage 3 on the oracle's K': bit-exact mask and lists
+    pbs.block_mask(p, st["Q"], pipe.Kp, pipe.mask_bits, pipe.row_cnt, pipe.col_idx, pipe.ws3)
+    torch.cuda.synchronize()
+    assert np.array_equal(mask_from_bits(pipe.mask_bits, w.T), st["mask"])
+    cnt = pipe.row_cnt.cpu().numpy()
+    assert np.array_equal(cnt, st["row_cnt"])
+    cols = pipe.col_idx.cpu().numpy()
+    valid = np.arange(w.T)[None, None, None, :] < cnt[..., None]
+    assert np.array_equal(np.where(valid, cols, -1), st["col_idx"])
+    # block accounting: every allowed block under segments is R^2 G(G+1)/2 (+ the plain causal tail)
+    R, G = w.segment // w.block, w.n // w.segment
+    assert int(st["row_cnt"].max()) <= w.T and int(st["row_cnt"].sum()) <= w.h_q * (R * R * G * (G + 1) // 2)
+
+
+@pytest.mark.parametrize("name", ["c2", "c3"])
+def test_full_size_attention_on_sampled_rows(oracle, name):
+    st = _setup(name, oracle)
+    w, p, pipe = st["w"], st["p"], st["pipe"]
+    T, R = w.T, w.segment // w.block
+    rng = np.random.default_rng(5)
+    picks = [0, 1, R - 1, R, T // 2, T - R - 1, T - R, T - 2, T - 1] + rng.integers(0, T, size=7).tolist()
+    rows = [[0, int(rng.integers(0, w.h_q)), int(i)] for i in picks]
+    rows += [[0, h, T - 1] for h in (0, w.h_q - 1)]          # the longest rows of the first and last head
+    # oracle's intermediates in, GPU attention out
+    Kp_d, Vt_d = to_dev(st["Kp"], "bf16"), to_dev(vt_layout(st["Vp"], w.block), "bf16")
+    Op, lse = pbs.attn_fwd(p, st["Q"], Kp_d, Vt_d, None, i32_dev(st["kidx"]), i32_dev(st["row_cnt"]),
+                           i32_dev(st["col_idx"]), pipe.Op, want_lse=True)
+    torch.cuda.synchronize()
+    want, want_lse = oracle.attn_rows(w.Q, st["Kp"], st["Vp"], None, st["kidx"], st["row_cnt"], st["col_idx"],
+                                      w.block, rows, want_lse=True)
+    for u, (b, h, i) in enumerate(rows):
+        sl = slice(i * w.block, (i + 1) * w.block)
+        check_close(to_host(Op[b, h, sl]), want[u], "bf16", "%s row (%d,%d,%d)" % (name, b, h, i))
+        np.testing.assert_allclose(lse[b, h, sl].cpu().numpy(), want_lse[u], rtol=0, atol=2e-2)
+    # properties that hold at any size: finite everywhere, and every output row is a convex combination of V rows
+    assert torch.isfinite(Op).all()
+    vmax = st["V"].float().abs().amax(dim=2)                 # [1,Hkv,d]
+    bound = vmax.repeat_interleave(w.h_q // w.h_kv, dim=1)[:, :, None, :] * 1.01 + 1e-3
+    assert (Op.float().abs() <= bound).all()
