@@ -27,57 +27,103 @@ __device__ inline int swap23(int m) { return (m & ~12) | ((m & 4) << 1) | ((m & 
 // ---------------------------------------------------------------------------------------------
 // MFMA kernel.  BLOCK = block size; WAVES = waves per workgroup; each wave owns BLOCK / WAVES query rows.
 // Key blocks are consumed in sub-tiles of KT = 64 keys.  K' and V'^T sub-tiles are double-buffered in LDS and
-// filled by asynchronous global->LDS loads (no registers, no LDS store instructions): while sub-tile s is being
+// filled by asynchronous buffer->LDS loads (no registers, no LDS store instructions): while sub-tile s is being
 // multiplied, sub-tile s+1 is in flight.  One barrier per sub-tile.
-// grid = 1-D, see the workgroup decoding at the top of the kernel (mfma_grid() on the host).
+// grid = 1-D, see the workgroup decoding at the top of the kernel.
+//
+// Softmax with a lazily updated reference.  On the common path an element costs one v_fma_f32 (s*c - mref), one
+// v_exp_f32, and per pair one v_cvt_pk_bf16_f32 and one v_dot2c_f32_bf16 (row sum of the ROUNDED probabilities):
+// no row maximum, no rescale of O.  Any reference gives the same softmax as long as nothing overflows, so the
+// reference only has to move when a row sum grows past 2^16; that, a block that needs the token-level causal
+// mask, and a query that has not met a visible key yet take the exact path (row maximum, reference update,
+// rescale of O and l).
 // ---------------------------------------------------------------------------------------------
 constexpr int KT = 64;                                     // keys per sub-tile
 constexpr int kListChunk = 1024;                           // listed blocks staged in LDS at a time
 constexpr int kXcds = 8;                                   // accelerator dies, each with a private L2
 constexpr int kCohort = 64;                                // workgroups resident per XCD (32 CUs x 2)
+constexpr float kBigRowSum = 65536.0f;                     // lazy-reference overflow guard
 
-typedef const __attribute__((address_space(1))) void *gptr_t;
 typedef __attribute__((address_space(3))) void *lptr_t;
 
-// Issue this wave's share of the loads of one sub-tile.  One instruction moves 64 lanes x 16 bytes into 1 KiB of
-// contiguous LDS; which global chunk a lane fetches is chosen so that the LDS image is the swizzled tile:
-//   K' sub-tile  [KT rows][128 d]  (256-byte rows): LDS row r holds key (r & ~31) | swap23(r & 31),
-//                                                   16-byte chunk c of that key sits at chunk c ^ (r & 15);
-//   V'^T sub-tile [128 rows][KT keys] (128-byte rows): chunk c of row r sits at chunk c ^ ((r >> 1) & 7).
-template <int BLOCK, int WAVES>
-__device__ inline void issue_subtile(bf16_t *kbuf, bf16_t *vbuf, int *kpos, const bf16_t *Kh, const bf16_t *Vh,
-                                     const int32_t *kih, int j, int half, int n, bool masked, int wave, int lane)
+// Buffer descriptors (base, size in bytes) of one kv head's K', V'^T and key positions.  A load is
+// "descriptor base + scalar tile offset + per-lane offset": no 64-bit vector arithmetic, and anything past the end
+// of K' or of the positions reads as zero (such key slots are rejected by index in the exact softmax path).
+struct TileBuffers {
+    __amdgpu_buffer_rsrc_t k, v, pos;
+};
+
+template <int BLOCK>
+__device__ inline TileBuffers tile_buffers(const bf16_t *Kh, const bf16_t *Vh, const int32_t *kih, int n, int T)
 {
-    constexpr int D = 128;
-    constexpr int KI = KT * D * 2 / 1024;                 // 16 instructions for K'
-    constexpr int VI = D * KT * 2 / 1024;                 // 16 instructions for V'^T
-#pragma unroll
-    for (int x = wave; x < KI; x += WAVES) {
-        const int r = 4 * x + (lane >> 4);
-        const int pc = lane & 15;
-        const int key = (r & ~31) | swap23(r & 31);
-        int slot = j * BLOCK + half * KT + key;
-        if (slot >= n) slot = n - 1;                      // clamped; such keys are masked before the softmax
-        const bf16_t *src = Kh + (size_t)slot * D + ((pc ^ (r & 15)) << 3);
-        __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(kbuf + x * 512), 16, 0, 0);
-    }
-#pragma unroll
-    for (int x = wave; x < VI; x += WAVES) {
-        const int r = 8 * x + (lane >> 3);
-        const int pc = lane & 7;
-        const bf16_t *src = Vh + ((size_t)j * D + r) * BLOCK + half * KT + ((pc ^ ((r >> 1) & 7)) << 3);
-        __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(vbuf + x * 512), 16, 0, 0);
-    }
-    if (masked && wave == WAVES - 1) {                    // original positions of the sub-tile's 64 keys
-        int slot = j * BLOCK + half * KT + lane;
-        if (slot >= n) slot = n - 1;                      // clamped; slots >= n are rejected by index below
-        __builtin_amdgcn_global_load_lds((gptr_t)(kih + slot), (lptr_t)kpos, 4, 0, 0);
-    }
+    constexpr int kRawDword = 0x00020000;                  // gfx9 descriptor word 3: raw 32-bit data format
+    TileBuffers b;
+    b.k = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(Kh), 0, n * 256, kRawDword);
+    b.v = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(Vh), 0, T * 128 * BLOCK * 2, kRawDword);
+    b.pos = __builtin_amdgcn_make_buffer_rsrc(const_cast<int32_t *>(kih), 0, n * 4, kRawDword);
+    return b;
 }
 
-// Barrier that also publishes the asynchronous global->LDS loads of every wave: the loads of a wave are only
-// counted by that wave's own vmcnt, and the workgroup-scope fence of __syncthreads() does not wait on them, so
-// each wave drains its own counter (s_waitcnt vmcnt(0), gfx9 encoding) before it arrives at the barrier.
+// LDS tiles are row-padded by 16 bytes instead of XOR-swizzled: K' sub-tile rows are 272 bytes (256 + 16), V'^T
+// sub-tile rows 144 bytes (128 + 16).  Sixteen consecutive rows then start 4 (resp. 36 mod 64) banks apart, so the
+// 16-lane groups of a ds_read_b128 hit 64 distinct banks, and -- unlike a swizzle -- the address of fragment k is
+// "lane base + k * 32 bytes", an immediate offset: one address register per tile instead of one per fragment.
+// LDS row r of the K' tile holds key (r & ~31) | swap23(r & 31).
+constexpr int kKRowB = 272, kVRowB = 144;                  // padded row sizes in bytes
+constexpr int kKTileB = KT * kKRowB;                       // 17408 = 17 KiB
+constexpr int kVTileB = 128 * kVRowB;                      // 18432 = 18 KiB
+constexpr int kKLoads = kKTileB / 1024, kVLoads = kVTileB / 1024;
+
+// Per-lane global byte offsets of this wave's chunks inside a sub-tile, computed once.  One load instruction
+// moves 64 lanes x 16 bytes into 1 KiB of CONTIGUOUS LDS; the lane decides which global chunk lands there, so the
+// LDS image is the padded tile (lanes that fall on padding bytes fetch chunk 0 of their row, harmlessly).
+template <int WAVES>
+struct LaneOffsets {
+    uint32_t k[(kKLoads + WAVES - 1) / WAVES], v[(kVLoads + WAVES - 1) / WAVES];
+};
+
+template <int BLOCK, int WAVES>
+__device__ inline LaneOffsets<WAVES> lane_offsets(int wave, int lane)
+{
+    LaneOffsets<WAVES> o;
+#pragma unroll
+    for (int y = 0; y < (kKLoads + WAVES - 1) / WAVES; ++y) {
+        const int pos = (wave + WAVES * y) * 1024 + lane * 16;
+        const int r = pos / kKRowB, col = pos % kKRowB;
+        const int key = (r & ~31) | swap23(r & 31);
+        o.k[y] = (uint32_t)(key * 256 + (col < 256 ? col : 0));
+    }
+#pragma unroll
+    for (int y = 0; y < (kVLoads + WAVES - 1) / WAVES; ++y) {
+        const int pos = (wave + WAVES * y) * 1024 + lane * 16;
+        const int r = pos / kVRowB, col = pos % kVRowB;
+        o.v[y] = (uint32_t)(r * (BLOCK * 2) + (col < 128 ? col : 0));
+    }
+    return o;
+}
+
+template <int BLOCK, int WAVES>
+__device__ inline void issue_subtile(unsigned char *kbuf, unsigned char *vbuf, int *kpos, const TileBuffers &buf,
+                                     const LaneOffsets<WAVES> &off, int j, int half, bool masked, int wave, int lane)
+{
+    const int slot0 = j * BLOCK + half * KT;               // uniform
+#pragma unroll
+    for (int y = 0; y < (kKLoads + WAVES - 1) / WAVES; ++y)
+        if (wave + WAVES * y < kKLoads)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(buf.k, (lptr_t)(kbuf + (wave + WAVES * y) * 1024), 16, off.k[y],
+                                                     slot0 * 256, 0, 0);
+#pragma unroll
+    for (int y = 0; y < (kVLoads + WAVES - 1) / WAVES; ++y)
+        if (wave + WAVES * y < kVLoads)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(buf.v, (lptr_t)(vbuf + (wave + WAVES * y) * 1024), 16, off.v[y],
+                                                     j * (128 * BLOCK * 2) + half * (KT * 2), 0, 0);
+    if (masked && wave == WAVES - 1)                       // original positions of the sub-tile's 64 keys
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(buf.pos, (lptr_t)kpos, 4, lane * 4, slot0 * 4, 0, 0);
+}
+
+// Barrier that also publishes the asynchronous LDS loads of every wave: the loads of a wave are only counted by
+// that wave's own vmcnt, and the workgroup-scope fence of __syncthreads() does not wait on them, so each wave
+// drains its own counter (s_waitcnt vmcnt(0), gfx9 encoding) before it arrives at the barrier.
 __device__ inline void sync_tiles()
 {
     __builtin_amdgcn_s_waitcnt(0x0F70);
@@ -87,106 +133,161 @@ __device__ inline void sync_tiles()
 template <int NT>
 struct AttnState {
     floatx16 acc_o[4][NT];
-    float m2[NT], l[NT];
+    float mref[NT], l[NT];  // reference (log2 units) and sum of exp2(s*c - mref), this lane's half of the keys
+    bool seen[NT];          // the query has met at least one visible key, i.e. mref is meaningful
 };
 
-// One sub-tile: S^T = K' Q'^T, causal mask if needed, online softmax, O^T += V'^T P^T.
-template <int BLOCK, int NT>
-__device__ inline void compute_subtile(AttnState<NT> &st, const bf16_t *kbuf, const bf16_t *vbuf,
-                                       const bf16x8 (&qf)[NT][8], const int (&qpos)[NT], const int *kpos, int j,
-                                       int half, int n, bool masked, float c2, int ln, int lh)
+// p = exp2(s * c2 - shift) for 8 consecutive keys, packed to bf16; rsum += the rounded values
+__device__ inline bf16x8 exp2_pack8(const floatx16 &s, int base, float c2, float shift, float &rsum)
 {
-    constexpr int D = 128;
-    floatx16 acc_s[2][NT];
+    const bf16x2 ones = {(bf16_t)1.0f, (bf16_t)1.0f};
+    bf16x8 pk;
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
+    for (int y = 0; y < 4; ++y) {
+        floatx2 pr = {__builtin_amdgcn_exp2f(__builtin_fmaf(s[base + 2 * y], c2, -shift)),
+                      __builtin_amdgcn_exp2f(__builtin_fmaf(s[base + 2 * y + 1], c2, -shift))};
+        const bf16x2 t2 = __builtin_convertvector(pr, bf16x2);
+        rsum = __builtin_amdgcn_fdot2_f32_bf16(t2, ones, rsum, false);
+        pk[2 * y] = t2[0];
+        pk[2 * y + 1] = t2[1];
+    }
+    return pk;
+}
+
+// One sub-tile: S^T = K' Q'^T, softmax relative to the lane's reference, O^T += V'^T P^T.
+template <int BLOCK, int NT>
+__device__ inline void compute_subtile(AttnState<NT> &st, const unsigned char *kbuf, const unsigned char *vbuf,
+                                       const bf16x8 (&qf)[NT][8], const int (&qpos)[NT], const int *kpos, int room,
+                                       bool masked, float c2, int ln, int lh)
+{
+    const unsigned char *kl = kbuf + ln * kKRowB + lh * 16;      // this lane's row / half inside a 32-key tile
+    const unsigned char *vl = vbuf + ln * kVRowB + lh * 16;
+    // S^T of one 32-key tile (8 MFMAs per query tile).  Operand fragments are fetched from LDS four at a time
+    // (16 registers), the next four while the current four are being multiplied; the scheduling barriers keep the
+    // compiler from hoisting every load to the top (registers) or sinking each one next to its MFMA (latency).
+    auto s_tile = [&](floatx16 (&acc)[NT], int mt) {
+        bf16x8 fa[4], fb[4];
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
+        for (int x = 0; x < 4; ++x) fa[x] = *reinterpret_cast<const bf16x8 *>(kl + mt * 32 * kKRowB + x * 32);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int x = 0; x < 16; ++x) acc_s[mt][nt][x] = 0.0f;
+        for (int x = 0; x < 4; ++x) fb[x] = *reinterpret_cast<const bf16x8 *>(kl + mt * 32 * kKRowB + (4 + x) * 32);
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt) {
-        const int lrow = 32 * mt + ln;
-#pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            const bf16x8 a = *reinterpret_cast<const bf16x8 *>(kbuf + lrow * D + (((2 * k + lh) ^ (lrow & 15)) << 3));
+        for (int x = 0; x < 4; ++x)
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt)
-                acc_s[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[nt][k], acc_s[mt][nt], 0, 0, 0);
-        }
-    }
-    // acc_s[mt][nt][x]: key (within the sub-tile) = 32 mt + 16 (x / 8) + 8 h + (x % 8), query = q0 + 32 nt + n
-    if (masked) {
-        const int room = n - (j * BLOCK + half * KT);     // key slots of this sub-tile that exist
+                acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[x], qf[nt][x], x == 0 ? floatx16{0} : acc[nt], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
+        for (int x = 0; x < 4; ++x)
 #pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                const int k8 = 32 * mt + 16 * u + 8 * lh;  // 8 consecutive keys of this lane
-                const int4 a = *reinterpret_cast<const int4 *>(kpos + k8);
-                const int4 b = *reinterpret_cast<const int4 *>(kpos + k8 + 4);
-                const int kp[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-#pragma unroll
-                for (int x = 0; x < 8; ++x)
-#pragma unroll
-                    for (int nt = 0; nt < NT; ++nt)
-                        if (kp[x] > qpos[nt] || k8 + x >= room) acc_s[mt][nt][8 * u + x] = -INFINITY;
-            }
-    }
-    // online softmax in the log2 domain; P is packed to bf16 straight into the second product's B operand
+            for (int nt = 0; nt < NT; ++nt)
+                acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[x], qf[nt][4 + x], acc[nt], 0, 0, 0);
+    };
+    // acc[nt][x] of tile mt: key (within the sub-tile) = 32 mt + 16 (x / 8) + 8 h + (x % 8), query = q0 + 32 nt + n
+
     bf16x8 pf[NT][4];
+    bool all_seen = true;
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-        float rmax = -INFINITY;
+    for (int nt = 0; nt < NT; ++nt) all_seen = all_seen && st.seen[nt];
+    bool exact = masked || !__all(all_seen);
+    if (!exact) {
+        // common path: p = exp2(S), one 32-key tile at a time (the scores of a tile die as soon as they are packed)
+        float rsum[NT];
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
+        for (int nt = 0; nt < NT; ++nt) rsum[nt] = 0.0f;
 #pragma unroll
-            for (int x = 0; x < 16; ++x) rmax = fmaxf(rmax, acc_s[mt][nt][x]);
-        rmax = fmaxf(rmax, __shfl_xor(rmax, 32, 64));
-        const float mnew = fmaxf(st.m2[nt], rmax * c2);
-        const float muse = mnew == -INFINITY ? 0.0f : mnew;
-        const float alpha = __builtin_amdgcn_exp2f(st.m2[nt] - muse);
-        float rsum = 0.0f;
-#pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                floatx2 pr[4];
-#pragma unroll
-                for (int x = 0; x < 8; ++x) {
-                    const float p = __builtin_amdgcn_exp2f(acc_s[mt][nt][8 * u + x] * c2 - muse);
-                    rsum += p;
-                    pr[x >> 1][x & 1] = p;
-                }
-                bf16x8 pk;
-#pragma unroll
-                for (int y = 0; y < 4; ++y) {
-                    const bf16x2 t2 = __builtin_convertvector(pr[y], bf16x2);
-                    pk[2 * y] = t2[0];
-                    pk[2 * y + 1] = t2[1];
-                }
-                pf[nt][2 * mt + u] = pk;
-            }
-        st.l[nt] = st.l[nt] * alpha + rsum;
-        st.m2[nt] = mnew;
-        if (__any(alpha != 1.0f)) {                        // the running maximum moved for some query of the wave
-#pragma unroll
-            for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-                for (int x = 0; x < 16; ++x) st.acc_o[dt][nt][x] *= alpha;
-        }
-    }
-#pragma unroll
-    for (int dt = 0; dt < 4; ++dt) {
-        const int row = 32 * dt + ln;
-        const int sw = (row >> 1) & 7;
-#pragma unroll
-        for (int k2 = 0; k2 < 4; ++k2) {
-            const bf16x8 a = *reinterpret_cast<const bf16x8 *>(vbuf + row * KT + (((2 * k2 + lh) ^ sw) << 3));
+        for (int mt = 0; mt < 2; ++mt) {
+            floatx16 acc[NT];
+            s_tile(acc, mt);
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt)
-                st.acc_o[dt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[nt][k2], st.acc_o[dt][nt], 0, 0, 0);
+#pragma unroll
+                for (int u = 0; u < 2; ++u) pf[nt][2 * mt + u] = exp2_pack8(acc[nt], 8 * u, c2, st.mref[nt], rsum[nt]);
         }
+        bool big = false;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) big = big || !(rsum[nt] <= kBigRowSum);
+        if (__any(big)) {
+            exact = true;                                  // a row outgrew its reference: redo this sub-tile exactly
+        } else {
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) st.l[nt] += rsum[nt];
+        }
+    }
+    if (exact) {
+        floatx16 acc_s[2][NT];
+        s_tile(acc_s[0], 0);
+        s_tile(acc_s[1], 1);
+        if (masked) {
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    const int k8 = 32 * mt + 16 * u + 8 * lh;  // 8 consecutive keys of this lane
+                    const int4 a = *reinterpret_cast<const int4 *>(kpos + k8);
+                    const int4 b = *reinterpret_cast<const int4 *>(kpos + k8 + 4);
+                    const int kp[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+                    const int lim = room - k8;                 // keys x >= lim of this group do not exist
+#pragma unroll
+                    for (int x = 0; x < 8; ++x)
+#pragma unroll
+                        for (int nt = 0; nt < NT; ++nt)
+                            if (kp[x] > qpos[nt] || x >= lim) acc_s[mt][nt][8 * u + x] = -INFINITY;
+                }
+        }
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            float rmax = -INFINITY;
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                for (int x = 0; x < 16; ++x) rmax = fmaxf(rmax, acc_s[mt][nt][x]);
+            rmax = fmaxf(rmax, __shfl_xor(rmax, 32, 64));
+            const bool was = st.seen[nt];
+            const bool now = was || rmax != -INFINITY;
+            // move the reference up to the row maximum (first contact: set it to the maximum, whatever its sign)
+            const float mnew = now ? (was ? fmaxf(rmax * c2, st.mref[nt]) : rmax * c2) : 0.0f;
+            const float alpha = was ? __builtin_amdgcn_exp2f(st.mref[nt] - mnew) : 1.0f;
+            float rsum = 0.0f;
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                for (int u = 0; u < 2; ++u) pf[nt][2 * mt + u] = exp2_pack8(acc_s[mt][nt], 8 * u, c2, mnew, rsum);
+            st.l[nt] = st.l[nt] * alpha + rsum;
+            st.seen[nt] = now;
+            st.mref[nt] = mnew;
+            if (__any(alpha != 1.0f)) {
+#pragma unroll
+                for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+                    for (int x = 0; x < 16; ++x) st.acc_o[dt][nt][x] *= alpha;
+            }
+        }
+    }
+
+    {
+        bf16x8 fa[4], fb[4];
+#pragma unroll
+        for (int x = 0; x < 4; ++x) fa[x] = *reinterpret_cast<const bf16x8 *>(vl + x * 32);
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt) {                   // one 32-row tile of O^T per step, 4 fragments each
+            bf16x8(&cur)[4] = (dt & 1) ? fb : fa;
+            bf16x8(&nxt)[4] = (dt & 1) ? fa : fb;
+            __builtin_amdgcn_sched_barrier(0);
+            if (dt < 3) {
+#pragma unroll
+                for (int x = 0; x < 4; ++x)
+                    nxt[x] = *reinterpret_cast<const bf16x8 *>(vl + (dt + 1) * 32 * kVRowB + x * 32);
+            }
+#pragma unroll
+            for (int k2 = 0; k2 < 4; ++k2)
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+                    st.acc_o[dt][nt] =
+                        __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur[k2], pf[nt][k2], st.acc_o[dt][nt], 0, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
     }
 }
 
@@ -201,10 +302,10 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
     constexpr int SUBS = BLOCK / KT;               // sub-tiles per key block
     static_assert(NT >= 1 && SUBS >= 1, "unsupported tiling");
 
-    __shared__ __align__(16) bf16_t kbuf0[KT * D], kbuf1[KT * D];   // 16 KiB each
-    __shared__ __align__(16) bf16_t vbuf0[D * KT], vbuf1[D * KT];   // 16 KiB each
+    __shared__ __align__(16) unsigned char kbuf0[kKTileB], kbuf1[kKTileB];   // 17 KiB each
+    __shared__ __align__(16) unsigned char vbuf0[kVTileB], vbuf1[kVTileB];   // 18 KiB each
     __shared__ __align__(16) int kpos0[KT], kpos1[KT];
-    __shared__ int jl[kListChunk];                                   // validated block list, -1 = skip
+    __shared__ int jl[kListChunk];                                            // validated block list, -1 = skip
 
     // Workgroup -> (query head, query block).  Workgroups are handed to the 8 XCDs round-robin by linear id and
     // every XCD has its own L2, so the id is decoded as (xcd, slot): the 64 workgroups that are resident on one XCD
@@ -224,13 +325,16 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
     const int b = unit / g.h_kv, hq = (unit % g.h_kv) * g.r + mrow % g.r;
     const int bhq = b * g.h_q + hq;
     const size_t bhk = unit;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int ln = lane & 31, lh = lane >> 5;
     const int q0 = i * BLOCK + wave * (BLOCK / WAVES);
+    const float c2 = g.scale * kLog2eF;
 
     // Q' fragments: lane (n, h) holds Q'[q0 + 32 nt + n][16 ks + 8 h .. +8]
     bf16x8 qf[NT][8];
     int qpos[NT];
+    AttnState<NT> st;
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
         const int qs = q0 + 32 * nt + ln;
@@ -239,27 +343,22 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
 #pragma unroll
         for (int k = 0; k < 8; ++k) qf[nt][k] = *reinterpret_cast<const bf16x8 *>(src + 16 * k);
         qpos[nt] = qs < g.n ? (qidx ? qidx[(size_t)bhq * g.n + qs] : qs) : -1;
-    }
-
-    AttnState<NT> st;
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-        st.m2[nt] = -INFINITY;
+        st.mref[nt] = 0.0f;
         st.l[nt] = 0.0f;
+        st.seen[nt] = qs >= g.n;                  // padding rows never hold the wave on the exact path
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
             for (int x = 0; x < 16; ++x) st.acc_o[dt][nt][x] = 0.0f;
     }
 
-    const float c2 = g.scale * kLog2eF;
     const int ni = allowed_cols(i, g);
     const int jmask = first_masked_col(i, g);
     const int cnt = min(row_cnt[(size_t)bhq * g.T + i], g.T);
     const int32_t *cols = col_idx + ((size_t)bhq * g.T + i) * g.T;
-    const bf16_t *Kh = Kp + bhk * (size_t)g.n * D;
-    const bf16_t *Vh = Vt + bhk * (size_t)g.T * D * BLOCK;
-    const int32_t *kih = kidx + bhk * (size_t)g.n;
+    const TileBuffers buf = tile_buffers<BLOCK>(Kp + bhk * (size_t)g.n * D, Vt + bhk * (size_t)g.T * D * BLOCK,
+                                                kidx + bhk * (size_t)g.n, g.n, g.T);
+    const LaneOffsets<WAVES> off = lane_offsets<BLOCK, WAVES>(wave, lane);
 
     // The list is consumed in chunks staged in LDS (read back with LDS loads, which do not wait on the
     // asynchronous tile loads).  Entries outside the columns the causal mask admits become -1 and are skipped;
@@ -274,38 +373,38 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
         }
         __syncthreads();
         const int total = len * SUBS;
+        auto block_at = [&](int s) -> int { return __builtin_amdgcn_readfirstlane(jl[s / SUBS]); };
         {
-            const int j0 = jl[0];
-            if (j0 >= 0)
-                issue_subtile<BLOCK, WAVES>(kbuf0, vbuf0, kpos0, Kh, Vh, kih, j0, 0, g.n, j0 >= jmask, wave, lane);
+            const int j0 = block_at(0);
+            if (j0 >= 0) issue_subtile<BLOCK, WAVES>(kbuf0, vbuf0, kpos0, buf, off, j0, 0, j0 >= jmask, wave, lane);
         }
         for (int s = 0; s < total; s += 2) {
             sync_tiles();                  // sub-tile s has landed in buffer 0; buffer 1 is free again
             if (s + 1 < total) {
-                const int j1 = jl[(s + 1) / SUBS];
+                const int j1 = block_at(s + 1);
                 if (j1 >= 0)
-                    issue_subtile<BLOCK, WAVES>(kbuf1, vbuf1, kpos1, Kh, Vh, kih, j1, (s + 1) % SUBS, g.n, j1 >= jmask,
-                                                wave, lane);
+                    issue_subtile<BLOCK, WAVES>(kbuf1, vbuf1, kpos1, buf, off, j1, (s + 1) % SUBS, j1 >= jmask, wave,
+                                                lane);
             }
             {
-                const int j = jl[s / SUBS];
+                const int j = block_at(s);
                 if (j >= 0)
-                    compute_subtile<BLOCK, NT>(st, kbuf0, vbuf0, qf, qpos, kpos0, j, s % SUBS, g.n, j >= jmask, c2, ln,
-                                               lh);
+                    compute_subtile<BLOCK, NT>(st, kbuf0, vbuf0, qf, qpos, kpos0, g.n - j * BLOCK - (s % SUBS) * KT,
+                                               j >= jmask, c2, ln, lh);
             }
             if (s + 1 >= total) break;
             sync_tiles();                  // sub-tile s+1 has landed in buffer 1; buffer 0 is free again
             if (s + 2 < total) {
-                const int j2 = jl[(s + 2) / SUBS];
+                const int j2 = block_at(s + 2);
                 if (j2 >= 0)
-                    issue_subtile<BLOCK, WAVES>(kbuf0, vbuf0, kpos0, Kh, Vh, kih, j2, (s + 2) % SUBS, g.n, j2 >= jmask,
-                                                wave, lane);
+                    issue_subtile<BLOCK, WAVES>(kbuf0, vbuf0, kpos0, buf, off, j2, (s + 2) % SUBS, j2 >= jmask, wave,
+                                                lane);
             }
             {
-                const int j = jl[(s + 1) / SUBS];
+                const int j = block_at(s + 1);
                 if (j >= 0)
-                    compute_subtile<BLOCK, NT>(st, kbuf1, vbuf1, qf, qpos, kpos1, j, (s + 1) % SUBS, g.n, j >= jmask,
-                                               c2, ln, lh);
+                    compute_subtile<BLOCK, NT>(st, kbuf1, vbuf1, qf, qpos, kpos1,
+                                               g.n - j * BLOCK - ((s + 1) % SUBS) * KT, j >= jmask, c2, ln, lh);
             }
         }
     }
@@ -329,7 +428,7 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
                     *reinterpret_cast<bf16x4 *>(dst + 32 * dt + 8 * gq + 4 * lh) = o4;
                 }
             if (lse && lh == 0)
-                lse[(size_t)bhq * g.n + qs] = lt > 0.0f ? (st.m2[nt] + log2f(lt)) * kLn2F : -INFINITY;
+                lse[(size_t)bhq * g.n + qs] = lt > 0.0f ? (st.mref[nt] + log2f(lt)) * kLn2F : -INFINITY;
         }
     }
 }
