@@ -4,10 +4,9 @@
 // multiply-add in the logits), so the mask does not depend on how a machine rounds lower precision:
 //   1. pool_kernel     block means of Q' and K' (HBM-bound; sums of bf16 values are exact in fp64).
 //                      Kbar is stored d-major ([head][e][T]) so that the next kernel reads it coalesced.
-//   2. select_kernel   one workgroup per (query head, query block i): logits against the allowed columns,
-//                      softmax, stable descending bitonic sort in LDS, inclusive scan, first k with
-//                      cumulative mass >= tau, forced blocks, then bit-mask words by wave ballot and the
-//                      ascending column list by prefix popcount.
+//   2. select_kernel   logits of up to four query heads of one group against the allowed columns, softmax,
+//                      the mass threshold by bisection (one wave per row), forced blocks, then bit-mask
+//                      words by wave ballot and the ascending column list by prefix popcount.
 #include "pbs_host.h"
 
 namespace pbs {
@@ -51,171 +50,197 @@ __global__ __launch_bounds__(256) void pool_kernel(const E *__restrict__ X, doub
 }
 
 // ---------------------------------------------------------------------------------------------
-// Selection.  LDS holds, for the p2 >= n_i padded columns: the probabilities (sort keys) and their
-// column indices.  Comparator: larger probability first, equal probabilities by smaller column.
+// Selection.  One workgroup per (kv head, chunk of RB query heads of its group, query block i): the RB rows
+// share the allowed columns and the pooled keys, so every Kbar value fetched feeds RB logits.  After the
+// logits, wave w owns row w and finishes it alone (no workgroup barriers): softmax, then the smallest
+// probability v* that is still kept, found by bisection instead of a sort.
+//
+// The kept set of Algorithm 2 is the shortest prefix of the order (probability descending, column ascending)
+// whose mass reaches tau.  With M(v) = sum of the probabilities >= v, v* is the largest v with M(v) >= tau:
+// every probability above v* is kept, and of the columns that tie at v* the first m by column index, m being
+// the number of additions of v* to M(> v*) that reach tau.  The bisection runs over the bit patterns of the
+// non-negative doubles between the smallest and the largest probability and stops as soon as a single
+// element, or a single bit pattern, is left in the bracket.
 // ---------------------------------------------------------------------------------------------
-__device__ inline bool before(double pa, int ia, double pb, int ib)
+struct MassCount {
+    double mass;
+    int cnt;
+};
+
+// mass and number of the row's probabilities >= v; pr is padded with -1 up to a multiple of 64
+__device__ inline MassCount mass_at_least(const double *pr, int ni64, int lane, double v)
 {
-    return pa > pb || (pa == pb && ia < ib);
+    double acc = 0.0;
+    int cnt = 0;
+    for (int j0 = 0; j0 < ni64; j0 += 64) {
+        const double x = pr[j0 + lane];
+        const bool ge = x >= v;
+        acc += ge ? x : 0.0;
+        cnt += __popcll(__ballot(ge));
+    }
+    return {wave_sum_dpp(acc), cnt};
 }
 
-template <int THREADS>
-__device__ inline double block_reduce_max(double v, double *red)
+template <int RB>
+__global__ __launch_bounds__(64 * RB) void select_kernel(const double *__restrict__ Qbar,    // [bhq][T][d]
+                                                         const double *__restrict__ KbarT,   // [bhkv][d][T]
+                                                         uint64_t *__restrict__ mask_bits,
+                                                         int32_t *__restrict__ row_cnt,
+                                                         int32_t *__restrict__ col_idx, Geo g, int chunks, int Tpad)
 {
-    v = wave_max(v);
-    __syncthreads();
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
-    __syncthreads();
-    double r = red[0];
-    for (int w = 1; w < THREADS / 64; ++w) r = fmax(r, red[w]);
-    return r;
-}
-
-template <int THREADS>
-__device__ inline double block_reduce_sum(double v, double *red)
-{
-    v = wave_sum(v);
-    __syncthreads();
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
-    __syncthreads();
-    double r = red[0];
-    for (int w = 1; w < THREADS / 64; ++w) r += red[w];
-    return r;
-}
-
-constexpr int kSelThreads = 256;
-
-__global__ __launch_bounds__(kSelThreads) void select_kernel(const double *__restrict__ Qbar,   // [bhq][T][d]
-                                                             const double *__restrict__ KbarT,  // [bhkv][d][T]
-                                                             uint64_t *__restrict__ mask_bits,
-                                                             int32_t *__restrict__ row_cnt,
-                                                             int32_t *__restrict__ col_idx, Geo g, int p2max)
-{
+    constexpr int THREADS = 64 * RB;
     extern __shared__ __align__(16) unsigned char smem_raw[];
-    double *prob = reinterpret_cast<double *>(smem_raw);             // [p2max]
-    double *csum = prob + p2max;                                     // [p2max] inclusive scan of sorted probs
-    int *order = reinterpret_cast<int *>(csum + p2max);              // [p2max]
-    unsigned char *sel = reinterpret_cast<unsigned char *>(order + p2max);   // [p2max]
-    __shared__ double q[128];
-    __shared__ double red[kSelThreads / 64];
-    __shared__ double wave_tot[kSelThreads / 64];
-    __shared__ int kmin;
-    __shared__ int word_cnt[kMaxT / 64];
-    __shared__ uint64_t words[kMaxT / 64];
+    double *prob = reinterpret_cast<double *>(smem_raw);             // [RB][Tpad]
+    __shared__ __align__(16) double qs[128 * RB];                    // [e][RB]
 
     const int i = blockIdx.x;
-    const int bhq = blockIdx.y;
-    const int b = bhq / g.h_q, hq = bhq % g.h_q;
-    const int bhk = b * g.h_kv + hq / g.r;
+    const int bhk = blockIdx.y / chunks, chunk = blockIdx.y % chunks;
+    const int b = bhk / g.h_kv, hk = bhk % g.h_kv;
+    const int rows = min(RB, g.r - chunk * RB);                      // query heads handled here
+    const int bhq0 = b * g.h_q + hk * g.r + chunk * RB;
     const int ni = allowed_cols(i, g);
-    int p2 = 1;
-    while (p2 < ni) p2 <<= 1;
     const int tid = threadIdx.x;
 
-    for (int e = tid; e < g.d; e += kSelThreads) q[e] = Qbar[((size_t)bhq * g.T + i) * g.d + e];
-    if (tid == 0) kmin = ni;
+    for (int idx = tid; idx < g.d * RB; idx += THREADS) {
+        const int e = idx / RB, row = idx % RB;
+        qs[idx] = row < rows ? Qbar[((size_t)(bhq0 + row) * g.T + i) * g.d + e] : 0.0;
+    }
     __syncthreads();
 
     // logits, plain multiply-then-add in the order e = 0..d-1
     const double *kt = KbarT + (size_t)bhk * g.d * g.T;
-    double lmax = -INFINITY;
-    for (int j = tid; j < ni; j += kSelThreads) {
-        double acc = 0.0;
-        for (int e = 0; e < g.d; ++e) acc = __dadd_rn(acc, __dmul_rn(q[e], kt[(size_t)e * g.T + j]));
-        const double v = __dmul_rn(acc, (double)g.scale);
-        prob[j] = v;
-        lmax = fmax(lmax, v);
-    }
-    lmax = block_reduce_max<kSelThreads>(lmax, red);
-    double lsum = 0.0;
-    for (int j = tid; j < ni; j += kSelThreads) {
-        const double ev = exp(prob[j] - lmax);
-        prob[j] = ev;
-        lsum += ev;
-    }
-    lsum = block_reduce_sum<kSelThreads>(lsum, red);
-    for (int j = tid; j < p2; j += kSelThreads) {
-        prob[j] = j < ni ? prob[j] / lsum : -1.0;          // padding sorts last
-        order[j] = j;
+    for (int j = tid; j < ni; j += THREADS) {
+        double acc[RB];
+#pragma unroll
+        for (int row = 0; row < RB; ++row) acc[row] = 0.0;
+        for (int e = 0; e < g.d; e += 8) {
+            double kv[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) kv[u] = kt[(size_t)(e + u) * g.T + j];
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+#pragma unroll
+                for (int row = 0; row < RB; ++row)
+                    acc[row] = __dadd_rn(acc[row], __dmul_rn(qs[(e + u) * RB + row], kv[u]));
+        }
+#pragma unroll
+        for (int row = 0; row < RB; ++row) prob[row * Tpad + j] = __dmul_rn(acc[row], (double)g.scale);
     }
     __syncthreads();
 
-    // bitonic sort, "before" order
-    for (int k = 2; k <= p2; k <<= 1) {
-        for (int jj = k >> 1; jj > 0; jj >>= 1) {
-            for (int t = tid; t < (p2 >> 1); t += kSelThreads) {
-                const int lo = t & (jj - 1);
-                const int a = ((t - lo) << 1) | lo;
-                const int bb = a | jj;
-                const bool asc = (a & k) == 0;
-                const double pa = prob[a], pb = prob[bb];
-                const int ia = order[a], ib = order[bb];
-                const bool a_first = before(pa, ia, pb, ib);
-                if (a_first != asc) { prob[a] = pb; prob[bb] = pa; order[a] = ib; order[bb] = ia; }
+    // from here on wave `row` works alone on its row
+    const int row = tid >> 6, lane = tid & 63;
+    if (row >= rows) return;
+    double *pr = prob + row * Tpad;
+    const int ni64 = (ni + 63) & ~63;
+    double lmax = -INFINITY;
+    for (int j = lane; j < ni; j += 64) lmax = fmax(lmax, pr[j]);
+    lmax = wave_max(lmax);
+    double lsum = 0.0, emin = INFINITY;
+    for (int j = lane; j < ni; j += 64) {
+        const double ev = exp(pr[j] - lmax);
+        pr[j] = ev;
+        lsum += ev;
+        emin = fmin(emin, ev);
+    }
+    lsum = wave_sum_dpp(lsum);
+    emin = -wave_max(-emin);
+    for (int j0 = 0; j0 < ni64; j0 += 64) {
+        const int j = j0 + lane;
+        pr[j] = j < ni ? pr[j] / lsum : -1.0;                // padding never counts
+    }
+    const double pmax = 1.0 / lsum, pmin = emin / lsum;      // exp(0) = 1 is the largest numerator
+
+    // vstar: smallest kept probability; above: mass and count of the probabilities > vstar; ties: columns at vstar
+    double vstar, above = 0.0;
+    int n_above = 0, n_tie;
+    int m;                                                   // ties kept, lowest columns first
+    if (!(g.tau > 0.0)) {                                    // the first cumulative sum already reaches tau
+        vstar = pmax;
+        n_tie = mass_at_least(pr, ni64, lane, pmax).cnt;
+        m = 1;
+    } else {
+        const MassCount all = mass_at_least(pr, ni64, lane, pmin);
+        if (all.mass < g.tau) {                              // never reached: everything is kept
+            vstar = -0.5;
+            n_above = ni;
+            n_tie = 0;
+            m = 0;
+        } else {
+            // invariant: M(lo) >= tau > M(hi); lo and hi are bit patterns of non-negative doubles
+            long long lo = __double_as_longlong(pmin), hi = __double_as_longlong(pmax) + 1;
+            int cnt_lo = all.cnt;
+            while (hi - lo > 1 && cnt_lo - n_above > 1) {
+                const long long mid = lo + ((hi - lo) >> 1);
+                const MassCount mc = mass_at_least(pr, ni64, lane, __longlong_as_double(mid));
+                if (mc.mass >= g.tau) { lo = mid; cnt_lo = mc.cnt; }
+                else { hi = mid; n_above = mc.cnt; above = mc.mass; }
             }
-            __syncthreads();
+            n_tie = cnt_lo - n_above;
+            if (hi - lo > 1) {                               // one element left in [lo, hi): it is vstar
+                const double hid = __longlong_as_double(hi);
+                double best = -1.0;
+                for (int j0 = 0; j0 < ni64; j0 += 64) {
+                    const double x = pr[j0 + lane];
+                    best = fmax(best, x < hid ? x : -1.0);
+                }
+                vstar = wave_max(best);
+            } else {
+                vstar = __longlong_as_double(lo);
+            }
+            double c = above;
+            m = 0;
+            do { c += vstar; ++m; } while (c < g.tau && m < n_tie);
         }
     }
 
-    // inclusive scan of the sorted probabilities: each thread owns a contiguous run
-    const int per = (ni + kSelThreads - 1) / kSelThreads;
-    const int t0 = min(ni, tid * per), t1 = min(ni, t0 + per);
-    double run = 0.0;
-    for (int t = t0; t < t1; ++t) run += prob[t];
-    // exclusive prefix of the per-thread sums: wave scan + wave totals
-    double incl = run;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        const double up = __shfl_up(incl, o, 64);
-        if ((tid & 63) >= o) incl += up;
-    }
-    if ((tid & 63) == 63) wave_tot[tid >> 6] = incl;
-    __syncthreads();
-    double offset = incl - run;
-    for (int w = 0; w < (tid >> 6); ++w) offset += wave_tot[w];
-    double c = offset;
-    int first = ni;                                          // first sorted position whose cumsum reaches tau
-    for (int t = t0; t < t1; ++t) {
-        c += prob[t];
-        csum[t] = c;
-        if (c >= g.tau && first == ni) first = t;
-    }
-    if (first < ni) atomicMin(&kmin, first + 1);
-    for (int j = tid; j < p2; j += kSelThreads) sel[j] = 0;
-    __syncthreads();
-    const int k = kmin;
-    for (int t = tid; t < k; t += kSelThreads) sel[order[t]] = 1;
-    __syncthreads();
-
-    // forced blocks and output
+    // forced blocks and output: mask words by ballot, ascending column list by prefix popcount
     const int seg = i / g.R;
     const int flo = seg < g.G ? seg * g.R : i;
     const int W = (g.T + 63) >> 6;
-    uint64_t *mrow = mask_bits + ((size_t)bhq * g.T + i) * W;
-    const int lane = tid & 63;
-    for (int w0 = 0; w0 < W; w0 += kSelThreads / 64) {
-        const int w = w0 + (tid >> 6);
+    const size_t orow = (size_t)(bhq0 + row) * g.T + i;
+    uint64_t *mrow = mask_bits + orow * W;
+    int32_t *crow = col_idx + orow * g.T;
+    const uint64_t below = (1ull << lane) - 1ull;
+    int base = 0, ties_seen = 0;
+    for (int w = 0; w < W; ++w) {
         const int j = w * 64 + lane;
+        const double x = j < ni ? pr[j] : -1.0;
+        const uint64_t tie_word = __ballot(x == vstar);
+        const int tie_rank = ties_seen + __popcll(tie_word & below);
+        ties_seen += __popcll(tie_word);
         bool on = false;
-        if (w < W && j < ni) on = sel[j] || j >= flo || (j == 0 && (g.flags & PBS_FLAG_FORCE_FIRST_BLOCK));
+        if (j < ni)
+            on = x > vstar || (x == vstar && tie_rank < m) || j >= flo ||
+                 (j == 0 && (g.flags & PBS_FLAG_FORCE_FIRST_BLOCK));
         const uint64_t word = __ballot(on);
-        if (w < W && lane == 0) { mrow[w] = word; words[w] = word; word_cnt[w] = __popcll(word); }
+        if (lane == 0) mrow[w] = word;
+        if (on) crow[base + __popcll(word & below)] = j;
+        base += __popcll(word);
     }
-    __syncthreads();
-    int32_t *crow = col_idx + ((size_t)bhq * g.T + i) * g.T;
-    for (int w0 = 0; w0 < W; w0 += kSelThreads / 64) {
-        const int w = w0 + (tid >> 6);
-        if (w >= W) continue;
-        int basec = 0;
-        for (int x = 0; x < w; ++x) basec += word_cnt[x];
-        const uint64_t word = words[w];
-        if ((word >> lane) & 1ull) crow[basec + __popcll(word & ((1ull << lane) - 1ull))] = w * 64 + lane;
+    if (lane == 0) row_cnt[orow] = base;
+}
+
+template <int RB>
+static pbs_status launch_select(const double *Qbar, const double *KbarT, uint64_t *mask_bits, int32_t *row_cnt,
+                                int32_t *col_idx, const Geo &g, hipStream_t s)
+{
+    const int chunks = (g.r + RB - 1) / RB;
+    const int Tpad = (g.T + 63) & ~63;
+    const size_t lds = (size_t)RB * Tpad * sizeof(double);
+    if (lds > 32 * 1024) {
+        static bool attr_set = false;
+        if (!attr_set) {
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(&select_kernel<RB>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    RB * kMaxT * (int)sizeof(double)) != hipSuccess)
+                return PBS_ERR_HIP;
+            attr_set = true;
+        }
     }
-    if (tid == 0) {
-        int total = 0;
-        for (int x = 0; x < W; ++x) total += word_cnt[x];
-        row_cnt[(size_t)bhq * g.T + i] = total;
-    }
+    hipLaunchKernelGGL(select_kernel<RB>, dim3(g.T, g.batch * g.h_kv * chunks), dim3(64 * RB), lds, s, Qbar, KbarT,
+                       mask_bits, row_cnt, col_idx, g, chunks, Tpad);
+    return launch_status();
 }
 
 size_t ws_block_mask(const pbs_problem *p)
@@ -255,19 +280,7 @@ extern "C" pbs_status pbs_block_mask(const pbs_problem *p, const void *Qp, const
                            g.d, g.block, g.T);
     }
     if ((st = launch_status()) != PBS_OK) return st;
-    int p2max = 1;
-    while (p2max < g.T) p2max <<= 1;
-    const size_t lds = (size_t)p2max * (8 + 8 + 4 + 1);
-    if (lds > 48 * 1024) {
-        static bool attr_set = false;
-        if (!attr_set) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void *>(&select_kernel),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, kMaxT * 21) != hipSuccess)
-                return PBS_ERR_HIP;
-            attr_set = true;
-        }
-    }
-    hipLaunchKernelGGL(select_kernel, dim3(g.T, nq), dim3(kSelThreads), lds, s, Qbar, KbarT, mask_bits, row_cnt,
-                       col_idx, g, p2max);
-    return launch_status();
+    if (g.r >= 3) return launch_select<4>(Qbar, KbarT, mask_bits, row_cnt, col_idx, g, s);
+    if (g.r == 2) return launch_select<2>(Qbar, KbarT, mask_bits, row_cnt, col_idx, g, s);
+    return launch_select<1>(Qbar, KbarT, mask_bits, row_cnt, col_idx, g, s);
 }

@@ -28,25 +28,33 @@ constexpr float kLog2e = 1.4426950408889634f;
 __global__ __launch_bounds__(256) void qhat_split_kernel(const bf16_t *__restrict__ Q, bf16_t *__restrict__ qsplit,
                                                          Geo g, int bl)
 {
-    const int bh = blockIdx.x;                      // batch * h_kv
+    // grid = (kQRows / 8, batch * h_kv): each workgroup converts 8 rows x 128 columns, 4 elements per thread
+    const int bh = blockIdx.y;
     const int b = bh / g.h_kv, h = bh % g.h_kv;
     bf16_t *hi = qsplit + (size_t)bh * 2 * kQRows * 128;
     bf16_t *lo = hi + kQRows * 128;
     const float mul = g.scale * kLog2e / (float)g.r;
-    for (int idx = threadIdx.x; idx < kQRows * 128; idx += blockDim.x) {
-        const int row = idx >> 7, e = idx & 127;
-        float acc = 0.0f;
-        if (row < bl)
-            for (int t = 0; t < g.r; ++t)
-                acc += (float)Q[(((size_t)b * g.h_q + h * g.r + t) * g.n + (g.n - bl + row)) * 128 + e];
-        const float v = acc * mul;
-        const bf16_t vh = (bf16_t)v;
-        const bf16_t vl = (bf16_t)(v - (float)vh);
-        const int chunk = (e >> 3) ^ (row & 15);
-        const int dst = row * 128 + chunk * 8 + (e & 7);
-        hi[dst] = vh;
-        lo[dst] = vl;
+    const int row = blockIdx.x * 8 + (threadIdx.x >> 5);
+    const int e0 = (threadIdx.x & 31) * 4;
+    float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (row < bl)
+        for (int t = 0; t < g.r; ++t) {
+            const bf16x4 v = *reinterpret_cast<const bf16x4 *>(
+                Q + (((size_t)b * g.h_q + h * g.r + t) * g.n + (g.n - bl + row)) * 128 + e0);
+#pragma unroll
+            for (int x = 0; x < 4; ++x) acc[x] += (float)v[x];
+        }
+    bf16x4 vh, vl;
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+        const float v = acc[x] * mul;
+        vh[x] = (bf16_t)v;
+        vl[x] = (bf16_t)(v - (float)vh[x]);
     }
+    const int chunk = (e0 >> 3) ^ (row & 15);
+    const int dst = row * 128 + chunk * 8 + (e0 & 7);
+    *reinterpret_cast<bf16x4 *>(hi + dst) = vh;
+    *reinterpret_cast<bf16x4 *>(lo + dst) = vl;
 }
 
 // Fragment of the split Qhat held in LDS: rows 32*tile + (lane & 31), contraction chunk for k-step ks.
@@ -69,7 +77,8 @@ __device__ inline void load_kfrags(bf16x8 (&kf)[8], const bf16_t *Kh, int key0, 
 
 // ------------------------------------------------------------------ MFMA path: sweep 1
 // partial[bh][wg][row] = (max2, sumexp2) over the keys of workgroup wg, log2 domain.
-__global__ __launch_bounds__(256) void scores_sweep1_kernel(const bf16_t *__restrict__ K,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void scores_sweep1_kernel(
+    const bf16_t *__restrict__ K,
                                                             const bf16_t *__restrict__ qsplit,
                                                             float2 *__restrict__ partial, Geo g)
 {
@@ -88,11 +97,13 @@ __global__ __launch_bounds__(256) void scores_sweep1_kernel(const bf16_t *__rest
 #pragma unroll
     for (int nt = 0; nt < 4; ++nt) { m[nt] = -INFINITY; l[nt] = 0.0f; }
     const int key_end = min(g.n, (wg + 1) * kKeysPerWg);
+    bf16x8 kf[8], kn[8];                                     // current fragments and the prefetched next tile
+    load_kfrags(kf, Kh, min(wg * kKeysPerWg + wave * 32, g.n - 1), g.n, lane);
     for (int key0 = wg * kKeysPerWg + wave * 32; key0 < key_end; key0 += 4 * 32) {
-        bf16x8 kf[8];
-        load_kfrags(kf, Kh, key0, g.n, lane);
+        load_kfrags(kn, Kh, min(key0 + 4 * 32, g.n - 1), g.n, lane);
 #pragma unroll
         for (int nt = 0; nt < 4; ++nt) {
+            asm volatile("" ::: "memory");                   // keeps the Qhat fragment reads inside the loop
             floatx16 acc = {0};
 #pragma unroll
             for (int ks = 0; ks < 8; ++ks) {
@@ -117,6 +128,8 @@ __global__ __launch_bounds__(256) void scores_sweep1_kernel(const bf16_t *__rest
                 m[nt] = mn;
             }
         }
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) kf[ks] = kn[ks];
     }
     // merge the two lane halves, then the four waves
 #pragma unroll
@@ -139,22 +152,36 @@ __global__ __launch_bounds__(256) void scores_sweep1_kernel(const bf16_t *__rest
 }
 
 // c[bh][row] = -max - log2(bl * sumexp) for row < bl, -inf for the padding rows.
-__global__ __launch_bounds__(kQRows) void scores_merge_kernel(const float2 *__restrict__ partial,
-                                                              float *__restrict__ cvec, int nwg, int bl)
+// 1024 threads: thread (grp, row) folds the partials grp, grp+8, ... of its row, then the 8 groups meet in LDS.
+__global__ __launch_bounds__(1024) void scores_merge_kernel(const float2 *__restrict__ partial,
+                                                            float *__restrict__ cvec, int nwg, int bl)
 {
-    const int bh = blockIdx.x, row = threadIdx.x;
-    float mn = -INFINITY;
-    for (int w = 0; w < nwg; ++w) mn = fmaxf(mn, partial[((size_t)bh * nwg + w) * kQRows + row].x);
-    float ln = 0.0f;
-    for (int w = 0; w < nwg; ++w) {
+    __shared__ float2 red[8][kQRows];
+    const int bh = blockIdx.x, row = threadIdx.x & (kQRows - 1), grp = threadIdx.x >> 7;
+    float mn = -INFINITY, ln = 0.0f;
+    for (int w = grp; w < nwg; w += 8) {
         const float2 pr = partial[((size_t)bh * nwg + w) * kQRows + row];
-        if (pr.x != -INFINITY) ln += pr.y * exp2f(pr.x - mn);
+        if (pr.x != -INFINITY) {
+            const float m2 = fmaxf(mn, pr.x);
+            ln = ln * exp2f(mn - m2) + pr.y * exp2f(pr.x - m2);
+            mn = m2;
+        }
     }
-    cvec[(size_t)bh * kQRows + row] = row < bl ? -mn - log2f((float)bl * ln) : -INFINITY;
+    red[grp][row] = make_float2(mn, ln);
+    __syncthreads();
+    if (grp == 0) {
+        float m2 = -INFINITY;
+        for (int q = 0; q < 8; ++q) m2 = fmaxf(m2, red[q][row].x);
+        float l2 = 0.0f;
+        for (int q = 0; q < 8; ++q)
+            if (red[q][row].x != -INFINITY) l2 += red[q][row].y * exp2f(red[q][row].x - m2);
+        cvec[(size_t)bh * kQRows + row] = row < bl ? -m2 - log2f((float)bl * l2) : -INFINITY;
+    }
 }
 
 // ------------------------------------------------------------------ MFMA path: sweep 2
-__global__ __launch_bounds__(256) void scores_sweep2_kernel(const bf16_t *__restrict__ K,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void scores_sweep2_kernel(
+    const bf16_t *__restrict__ K,
                                                             const bf16_t *__restrict__ qsplit,
                                                             const float *__restrict__ cvec,
                                                             float *__restrict__ scores, Geo g)
@@ -178,12 +205,14 @@ __global__ __launch_bounds__(256) void scores_sweep2_kernel(const bf16_t *__rest
     __syncthreads();
     const bf16_t *Kh = K + (size_t)bh * g.n * 128;
     const int key_end = min(g.n, (wg + 1) * kKeysPerWg);
+    bf16x8 kf[8], kn[8];
+    load_kfrags(kf, Kh, min(wg * kKeysPerWg + wave * 32, g.n - 1), g.n, lane);
     for (int key0 = wg * kKeysPerWg + wave * 32; key0 < key_end; key0 += 4 * 32) {
-        bf16x8 kf[8];
-        load_kfrags(kf, Kh, key0, g.n, lane);
+        load_kfrags(kn, Kh, min(key0 + 4 * 32, g.n - 1), g.n, lane);
         float sum = 0.0f;
 #pragma unroll
         for (int mt = 0; mt < 4; ++mt) {
+            asm volatile("" ::: "memory");                   // keeps the Qhat fragment reads inside the loop
             floatx16 acc = cinit[mt];
 #pragma unroll
             for (int ks = 0; ks < 8; ++ks) {
@@ -197,6 +226,8 @@ __global__ __launch_bounds__(256) void scores_sweep2_kernel(const bf16_t *__rest
         sum += __shfl_xor(sum, 32, 64);
         const int key = key0 + (lane & 31);
         if (lane < 32 && key < g.n) scores[(size_t)bh * g.n + key] = sum;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) kf[ks] = kn[ks];
     }
 }
 
@@ -374,11 +405,11 @@ extern "C" pbs_status pbs_key_scores(const pbs_problem *p, const void *Q, const 
     float2 *partial = reinterpret_cast<float2 *>(w);
     w += align_up((size_t)nbh * nwg * kQRows * sizeof(float2), kWsAlign);
     float *cvec = reinterpret_cast<float *>(w);
-    hipLaunchKernelGGL(qhat_split_kernel, dim3(nbh), dim3(256), 0, s, (const bf16_t *)Q, qsplit, g, bl);
+    hipLaunchKernelGGL(qhat_split_kernel, dim3(kQRows / 8, nbh), dim3(256), 0, s, (const bf16_t *)Q, qsplit, g, bl);
     if ((st = launch_status()) != PBS_OK) return st;
     hipLaunchKernelGGL(scores_sweep1_kernel, dim3(nwg, nbh), dim3(256), 0, s, (const bf16_t *)K, qsplit, partial, g);
     if ((st = launch_status()) != PBS_OK) return st;
-    hipLaunchKernelGGL(scores_merge_kernel, dim3(nbh), dim3(kQRows), 0, s, partial, cvec, nwg, bl);
+    hipLaunchKernelGGL(scores_merge_kernel, dim3(nbh), dim3(1024), 0, s, partial, cvec, nwg, bl);
     if ((st = launch_status()) != PBS_OK) return st;
     hipLaunchKernelGGL(scores_sweep2_kernel, dim3(nwg, nbh), dim3(256), 0, s, (const bf16_t *)K, qsplit, cvec, scores,
                        g);

@@ -85,4 +85,31 @@ __device__ inline double wave_sum(double v)
     return v;
 }
 
+// Sum over the wave without LDS traffic: butterflies inside each row of 16 lanes by DPP, then the four row totals
+// through scalar registers.  Every lane receives the same value, formed in the same order.
+__device__ inline double wave_sum_dpp(double v)
+{
+#define PBS_DPP_STEP(ctrl)                                                                      \
+    {                                                                                           \
+        const long long bits = __double_as_longlong(v);                                         \
+        const int lo = __builtin_amdgcn_update_dpp(0, (int)bits, ctrl, 0xf, 0xf, false);        \
+        const int hi = __builtin_amdgcn_update_dpp(0, (int)(bits >> 32), ctrl, 0xf, 0xf, false); \
+        v += __longlong_as_double(((long long)hi << 32) | (unsigned)lo);                        \
+    }
+    PBS_DPP_STEP(0xB1)    // quad_perm [1,0,3,2]
+    PBS_DPP_STEP(0x4E)    // quad_perm [2,3,0,1]
+    PBS_DPP_STEP(0x141)   // row_half_mirror
+    PBS_DPP_STEP(0x140)   // row_mirror
+#undef PBS_DPP_STEP
+    double rows[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const long long bits = __double_as_longlong(v);
+        const int lo = __builtin_amdgcn_readlane((int)bits, 16 * r);
+        const int hi = __builtin_amdgcn_readlane((int)(bits >> 32), 16 * r);
+        rows[r] = __longlong_as_double(((long long)hi << 32) | (unsigned)lo);
+    }
+    return (rows[0] + rows[1]) + (rows[2] + rows[3]);
+}
+
 }  // namespace pbs
