@@ -157,13 +157,14 @@ def block_mask(p, Qp, Kp, mask_bits=None, row_cnt=None, col_idx=None, ws=None):
     return mask_bits, row_cnt, col_idx
 
 
-def attn_fwd(p, Qp, Kp, Vt, qidx, kidx, row_cnt, col_idx, Op=None, lse=None, want_lse=False):
+def attn_fwd(p, Qp, Kp, Vt, qidx, kidx, row_cnt, col_idx, Op=None, lse=None, want_lse=False, ws=None):
     if Op is None:
         Op = torch.empty_like(Qp)
     if lse is None and want_lse:
         lse = torch.empty((p.batch, p.h_q, p.n), dtype=torch.float32, device=Qp.device)
+    ws, wp, wn = _ws_args(p, STAGE_ATTN_FWD, ws)
     _check(load_library().pbs_attn_fwd(ctypes.byref(p), _ptr(Qp), _ptr(Kp), _ptr(Vt), _ptr(qidx), _ptr(kidx),
-                                       _ptr(row_cnt), _ptr(col_idx), _ptr(Op), _ptr(lse), None, 0, _stream()),
+                                       _ptr(row_cnt), _ptr(col_idx), _ptr(Op), _ptr(lse), wp, wn, _stream()),
            "pbs_attn_fwd")
     return (Op, lse) if want_lse else Op
 
@@ -193,6 +194,7 @@ class Pipeline:
         self.Qp = torch.empty_like(self.Op) if use_sigma else None
         self.ws1 = alloc_workspace(p, STAGE_KEY_SCORES, device)
         self.ws3 = alloc_workspace(p, STAGE_BLOCK_MASK, device)
+        self.ws4 = alloc_workspace(p, STAGE_ATTN_FWD, device)
 
     def run(self, Q, K, V, qidx=None):
         p = self.p
@@ -200,5 +202,5 @@ class Pipeline:
         segment_permute(p, self.scores, K, V, self.kidx, self.Kp, self.Vt)
         Qp = Q if qidx is None else permute_rows(p, Q, qidx, self.Qp)
         block_mask(p, Qp, self.Kp, self.mask_bits, self.row_cnt, self.col_idx, self.ws3)
-        attn_fwd(p, Qp, self.Kp, self.Vt, qidx, self.kidx, self.row_cnt, self.col_idx, self.Op)
+        attn_fwd(p, Qp, self.Kp, self.Vt, qidx, self.kidx, self.row_cnt, self.col_idx, self.Op, ws=self.ws4)
         return unpermute(p, self.Op, qidx, self.O)

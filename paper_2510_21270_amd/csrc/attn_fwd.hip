@@ -14,6 +14,7 @@
 //
 // Vector kernel (fp32 arithmetic): every other supported dtype / d / block.
 #include <limits.h>
+#include <stdlib.h>
 
 #include "pbs_host.h"
 
@@ -107,14 +108,15 @@ __device__ inline void issue_subtile(unsigned char *kbuf, unsigned char *vbuf, i
                                      const LaneOffsets<WAVES> &off, int j, int half, bool masked, int wave, int lane)
 {
     const int slot0 = j * BLOCK + half * KT;               // uniform
+    // full rounds are unconditional; only the last, partial round of chunks tests the wave index
 #pragma unroll
     for (int y = 0; y < (kKLoads + WAVES - 1) / WAVES; ++y)
-        if (wave + WAVES * y < kKLoads)
+        if (y < kKLoads / WAVES || wave < kKLoads % WAVES)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(buf.k, (lptr_t)(kbuf + (wave + WAVES * y) * 1024), 16, off.k[y],
                                                      slot0 * 256, 0, 0);
 #pragma unroll
     for (int y = 0; y < (kVLoads + WAVES - 1) / WAVES; ++y)
-        if (wave + WAVES * y < kVLoads)
+        if (y < kVLoads / WAVES || wave < kVLoads % WAVES)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(buf.v, (lptr_t)(vbuf + (wave + WAVES * y) * 1024), 16, off.v[y],
                                                      j * (128 * BLOCK * 2) + half * (KT * 2), 0, 0);
     if (masked && wave == WAVES - 1)                       // original positions of the sub-tile's 64 keys
@@ -295,7 +297,8 @@ template <int BLOCK, int WAVES>
 __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVES / 2, WAVES / 2))) void attn_mfma_kernel(
     const bf16_t *__restrict__ Qp, const bf16_t *__restrict__ Kp, const bf16_t *__restrict__ Vt,
     const int32_t *__restrict__ qidx, const int32_t *__restrict__ kidx, const int32_t *__restrict__ row_cnt,
-    const int32_t *__restrict__ col_idx, bf16_t *__restrict__ Op, float *__restrict__ lse, Geo g)
+    const int32_t *__restrict__ col_idx, bf16_t *__restrict__ Op, float *__restrict__ lse,
+    const int32_t *__restrict__ only, Geo g)
 {
     constexpr int D = 128;
     constexpr int NT = BLOCK / WAVES / 32;         // 32-query tiles per wave
@@ -324,6 +327,7 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
     const int i = g.T - 1 - mrow / g.r;
     const int b = unit / g.h_kv, hq = (unit % g.h_kv) * g.r + mrow % g.r;
     const int bhq = b * g.h_q + hq;
+    if (only && only[(size_t)bhq * g.T + i] == 0) return;    // second pass: only the query blocks flagged by the first
     const size_t bhk = unit;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -517,7 +521,20 @@ __global__ __launch_bounds__(256) void attn_vector_kernel(
     }
 }
 
-size_t ws_attn_fwd(const pbs_problem *) { return 0; }
+// true when the 64-queries-per-wave kernel (attn_wide.hip) serves the problem
+static bool wide_path(const pbs_problem *p) { return p->dtype == PBS_BF16 && p->d == 128 && p->block == 128; }
+
+// The wide kernel leaves one flag per query block: blocks it could not finish with a fixed softmax reference.
+size_t ws_attn_fwd(const pbs_problem *p)
+{
+    if (!wide_path(p)) return 0;
+    const Geo g = make_geo(p);
+    return align_up((size_t)g.batch * g.h_q * g.T * sizeof(int32_t), kWsAlign);
+}
+
+pbs_status launch_attn_wide(const Geo &g, const void *Qp, const void *Kp, const void *Vt, const int32_t *qidx,
+                            const int32_t *kidx, const int32_t *row_cnt, const int32_t *col_idx, void *Op, float *lse,
+                            int32_t *redo, hipStream_t s);
 
 template <typename E, int D>
 static pbs_status launch_vector(const Geo &g, const void *Qp, const void *Kp, const void *Vt, const int32_t *qidx,
@@ -546,24 +563,33 @@ extern "C" pbs_status pbs_attn_fwd(const pbs_problem *p, const void *Qp, const v
                                    const int32_t *col_idx, void *Op, float *lse, void *ws, size_t ws_bytes,
                                    void *stream)
 {
-    (void)ws; (void)ws_bytes;
     pbs_status st = validate(p);
     if (st != PBS_OK) return st;
     if (!Qp || !Kp || !Vt || !kidx || !row_cnt || !col_idx || !Op) return PBS_ERR_NULL;
     if (!aligned16(Qp) || !aligned16(Kp) || !aligned16(Vt) || !aligned16(Op)) return PBS_ERR_SHAPE;
+    if ((st = check_ws(p, PBS_STAGE_ATTN_FWD, ws, ws_bytes)) != PBS_OK) return st;
     const Geo g = make_geo(p);
     hipStream_t s = (hipStream_t)stream;
     if (p->dtype == PBS_BF16 && p->d == 128 && (p->block == 128 || p->block == 64)) {
         const int ncoh = g.batch * g.h_kv * ((g.r * g.T + kCohort - 1) / kCohort);
         const dim3 mgrid((unsigned)(((ncoh + kXcds - 1) / kXcds) * kCohort * kXcds));
-        if (p->block == 128)
+        static const bool narrow_only = getenv("PBS_ATTN_NARROW") != nullptr;
+        if (p->block == 128) {
+            // first pass: every query block with a fixed softmax reference; second pass: the flagged blocks (none
+            // on ordinary inputs, then each workgroup of the second launch leaves at once) with the rescaling kernel
+            int32_t *redo = narrow_only ? nullptr : reinterpret_cast<int32_t *>(ws);
+            if (redo) {
+                st = launch_attn_wide(g, Qp, Kp, Vt, qidx, kidx, row_cnt, col_idx, Op, lse, redo, s);
+                if (st != PBS_OK) return st;
+            }
             hipLaunchKernelGGL((attn_mfma_kernel<128, 4>), mgrid, dim3(256), 0, s, (const bf16_t *)Qp,
                                (const bf16_t *)Kp, (const bf16_t *)Vt, qidx, kidx, row_cnt, col_idx, (bf16_t *)Op, lse,
-                               g);
-        else
+                               (const int32_t *)redo, g);
+        } else {
             hipLaunchKernelGGL((attn_mfma_kernel<64, 2>), mgrid, dim3(128), 0, s, (const bf16_t *)Qp,
                                (const bf16_t *)Kp, (const bf16_t *)Vt, qidx, kidx, row_cnt, col_idx, (bf16_t *)Op, lse,
-                               g);
+                               (const int32_t *)nullptr, g);
+        }
         return launch_status();
     }
     if (p->dtype == PBS_BF16)

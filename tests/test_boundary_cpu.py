@@ -96,7 +96,9 @@ def test_workspace_and_vt_sizes(lib):
     # pooled means of Q' and K' in fp64
     assert b.workspace_bytes(p, b.STAGE_BLOCK_MASK) >= (32 + 8) * T * 128 * 8
     assert b.workspace_bytes(p, b.STAGE_KEY_SCORES) > 0
-    assert b.workspace_bytes(p, b.STAGE_ATTN_FWD) == 0
+    # one redo flag per query block for the 64-queries-per-wave kernel (bf16, d = 128, block = 128), nothing otherwise
+    assert b.workspace_bytes(p, b.STAGE_ATTN_FWD) == 32 * T * 4
+    assert b.workspace_bytes(_p(block=64), b.STAGE_ATTN_FWD) == 0
     assert b.workspace_bytes(_p(h_q=30), b.STAGE_BLOCK_MASK) == 0
     # partial last block is padded in Vt
     q = _p(n=1000, block=64, segment=256, d=64, dtype="f32", h_q=2, h_kv=2)
