@@ -1,8 +1,8 @@
 // pbs_attn_fwd for bf16, d = 128, block = 128: the "wide" matrix-core kernel of Algorithm 1's main loop.
 //
 // Same transposed formulation as the kernel in attn_fwd.hip (S^T = K' Q'^T, O^T += V'^T P^T, one lane owns one query
-// of each 32-query tile, lazily updated softmax reference), but every wave owns 64 queries (two 32-query tiles) and
-// a workgroup is two waves, so that one wave runs per SIMD:
+// of each 32-query tile), but every wave owns 64 queries (two 32-query tiles) and a workgroup is two waves, so that
+// one wave runs per SIMD, and the softmax reference of a query is fixed at its first visible key (see kBigRowSum):
 //   * every K' / V'^T fragment read from LDS feeds two MFMAs instead of one;
 //   * the softmax arithmetic of a wave is interleaved, in its own instruction stream, with independent MFMAs (the
 //     scores of the NEXT sub-tile, the O^T update of the other query tile), so the matrix pipe does not depend on a
@@ -12,8 +12,8 @@
 // loads.  Iteration t:
 //     X:  S(t + 1) MFMAs        || softmax(t) of query tile 0 || V'^T fragment reads of sub-tile t
 //     Y:  O^T += ... tile 0     || softmax(t) of query tile 1 || K' fragment reads of sub-tile t + 2
-//     barrier (every load issued so far has landed; stage t is free) -> issue the loads of sub-tile t + 4
-//     Z:  O^T += ... tile 1
+//     Z:  O^T += ... tile 1     || barrier (every load issued so far has landed; stage t is free), then the
+//                                  loads of sub-tile t + 4 into stage t
 // A sub-tile that is not plain (token-level mask, queries without a visible key so far) first rewrites its scores
 // and references in a separate block, then goes through the same groups.
 #include "pbs_host.h"
@@ -27,7 +27,7 @@ constexpr int kKRowB = 272;                                // K' row in LDS: 256
 constexpr int kVRowB = 80;                                 // V'^T row in LDS: 32 keys x 2 bytes + 16 of padding
 constexpr int kKChunks = 9;                                // 32 x 272 = 8704 bytes -> nine 1 KiB load chunks
 constexpr int kVChunks = 10;                               // 128 x 80 = 10240 bytes
-constexpr int kLoadsPerWave = 10;                          // wave 0: 9 K' chunks + positions, wave 1: 10 V'^T chunks
+constexpr int kLoadsPerWave = 10;                          // 16-byte-per-lane loads a wave issues per stage
 constexpr int kList = 256;                                 // listed blocks staged in LDS at a time
 constexpr int kXcds = 8, kCohort = 64;
 constexpr float kLog2eF = 1.4426950408889634f;
@@ -46,7 +46,7 @@ typedef __attribute__((address_space(3))) void *lptr_t;
 struct __align__(16) Stage {
     unsigned char k[kKChunks * 1024];                      // row r holds key swap23(r) of the sub-tile
     unsigned char v[kVChunks * 1024];                      // row e holds V'^T[e][32 keys]
-    int pos[64];                                           // original positions of the keys (first 32 used)
+    int pos[64];                                           // original positions of the 32 keys (rest unused)
 };
 
 __device__ __forceinline__ int swap23(int m) { return (m & ~12) | ((m & 4) << 1) | ((m & 8) >> 1); }
@@ -55,45 +55,81 @@ struct TileBuffers {
     __amdgpu_buffer_rsrc_t k, v, pos;
 };
 
-// Per-lane byte offsets (inside one key block / one sub-tile) of the ten chunks this wave loads per stage.
+// The 19 chunks of a stage are loaded by the same ten instructions in both waves, with per-wave scalar operands:
+// wave 0 takes the nine K' chunks and V'^T chunk 9, wave 1 takes V'^T chunks 0..8 (and chunk 8 once more, so that
+// no branch on the wave index surrounds the instructions).  The 32 key positions ride on eight lanes of wave 0.
+// o[c]: per-lane byte offset, inside one key block / one sub-tile, of what this lane moves in load c.
 struct LaneOffsets {
     uint32_t o[kLoadsPerWave];
 };
+
+__device__ __forceinline__ uint32_t k_lane_offset(int chunk, int lane)
+{
+    const int pos = chunk * 1024 + lane * 16;
+    const int row = pos / kKRowB, col = pos % kKRowB;
+    return row < KS ? (uint32_t)(swap23(row) * 256 + (col < 256 ? col : 0)) : 0u;   // tail of chunk 8: padding
+}
+
+__device__ __forceinline__ uint32_t v_lane_offset(int chunk, int lane)
+{
+    const int pos = chunk * 1024 + lane * 16;
+    const int row = pos / kVRowB, col = pos % kVRowB;
+    return (uint32_t)(row * (BLOCK * 2) + (col < KS * 2 ? col : 0));
+}
 
 __device__ __forceinline__ LaneOffsets lane_offsets(int wave, int lane)
 {
     LaneOffsets r;
 #pragma unroll
-    for (int c = 0; c < kLoadsPerWave; ++c) {
-        const int pos = c * 1024 + lane * 16;
-        if (wave == 0) {
-            const int row = pos / kKRowB, col = pos % kKRowB;
-            r.o[c] = c < kKChunks ? (row < KS ? (uint32_t)(swap23(row) * 256 + (col < 256 ? col : 0)) : 0u)
-                                  : (uint32_t)(lane * 4);
-        } else {
-            const int row = pos / kVRowB, col = pos % kVRowB;
-            r.o[c] = (uint32_t)(row * (BLOCK * 2) + (col < KS * 2 ? col : 0));
-        }
-    }
+    for (int c = 0; c < kKChunks; ++c) r.o[c] = wave == 0 ? k_lane_offset(c, lane) : v_lane_offset(c, lane);
+    r.o[kKChunks] = v_lane_offset(wave == 0 ? 9 : 8, lane);
     return r;
 }
 
-// Loads of part P of block j into stage sg: ten instructions per wave, whatever the wave.
+// Scalar operands of the loads of part P of block j into stage sg.
+struct StageLoad {
+    __amdgpu_buffer_rsrc_t rsrc;       // loads 0..8
+    int soff, soff_v, soff_pos;        // scalar byte offsets: loads 0..8, load 9 (always V'^T), positions
+    unsigned char *dst, *dst9;         // LDS destinations of load 0 and of load 9
+};
+
 template <int P>
-__device__ __forceinline__ void issue_stage(Stage &sg, const TileBuffers &buf, const LaneOffsets &off, int j, int wave)
+__device__ __forceinline__ StageLoad stage_load(Stage &sg, const TileBuffers &buf, int j, int wave)
 {
-    if (wave == 0) {
-        const int slot0 = j * BLOCK + P * KS;
-#pragma unroll
-        for (int c = 0; c < kKChunks; ++c)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(buf.k, (lptr_t)(sg.k + c * 1024), 16, off.o[c], slot0 * 256, 0, 0);
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(buf.pos, (lptr_t)sg.pos, 4, off.o[kKChunks], slot0 * 4, 0, 0);
-    } else {
-        const int base = j * (D * BLOCK * 2) + P * (KS * 2);
-#pragma unroll
-        for (int c = 0; c < kVChunks; ++c)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(buf.v, (lptr_t)(sg.v + c * 1024), 16, off.o[c], base, 0, 0);
-    }
+    StageLoad a;
+    const int slot0 = j * BLOCK + P * KS;
+    a.soff_v = j * (D * BLOCK * 2) + P * (KS * 2);
+    a.soff_pos = slot0 * 4;
+    a.rsrc = wave == 0 ? buf.k : buf.v;
+    a.soff = wave == 0 ? slot0 * 256 : a.soff_v;
+    a.dst = wave == 0 ? sg.k : sg.v;
+    a.dst9 = sg.v + (wave == 0 ? 9 : 8) * 1024;
+    return a;
+}
+
+// load c of the ten
+template <int C>
+__device__ __forceinline__ void issue_load(const StageLoad &a, const TileBuffers &buf, const LaneOffsets &off)
+{
+    if (C < kKChunks) __builtin_amdgcn_raw_ptr_buffer_load_lds(a.rsrc, (lptr_t)(a.dst + C * 1024), 16, off.o[C], a.soff, 0, 0);
+    else __builtin_amdgcn_raw_ptr_buffer_load_lds(buf.v, (lptr_t)a.dst9, 16, off.o[kKChunks], a.soff_v, 0, 0);
+}
+
+// original positions of the sub-tile's 32 keys: 16 bytes on each of the first eight lanes of wave 0
+__device__ __forceinline__ void issue_positions(Stage &sg, const StageLoad &a, const TileBuffers &buf, int wave, int lane)
+{
+    if (wave == 0 && lane < 8) __builtin_amdgcn_raw_ptr_buffer_load_lds(buf.pos, (lptr_t)sg.pos, 16, lane * 16, a.soff_pos, 0, 0);
+}
+
+template <int P>
+__device__ __forceinline__ void issue_stage(Stage &sg, const TileBuffers &buf, const LaneOffsets &off, int j, int wave,
+                                            int lane)
+{
+    const StageLoad a = stage_load<P>(sg, buf, j, wave);
+    issue_load<0>(a, buf, off); issue_load<1>(a, buf, off); issue_load<2>(a, buf, off); issue_load<3>(a, buf, off);
+    issue_load<4>(a, buf, off); issue_load<5>(a, buf, off); issue_load<6>(a, buf, off); issue_load<7>(a, buf, off);
+    issue_load<8>(a, buf, off); issue_load<9>(a, buf, off);
+    issue_positions(sg, a, buf, wave, lane);
 }
 
 // Every asynchronous load of this wave has landed, then all waves meet: the stages loaded so far are complete.
@@ -109,35 +145,6 @@ struct State {
     bool seen[2];           // the query has met a visible key, i.e. mref is set
     bool bad;               // a probability outgrew the fixed reference: this query block is redone by the caller
 };
-
-// p = exp2(s * c2 - shift) for 8 consecutive keys, packed to bf16; rsum += the rounded values
-__device__ __forceinline__ bf16x8 exp2_pack8(const floatx16 &s, int base, float c2, float shift, float &rsum)
-{
-    const bf16x2 ones = {(bf16_t)1.0f, (bf16_t)1.0f};
-    bf16x8 pk;
-#pragma unroll
-    for (int y = 0; y < 4; ++y) {
-        floatx2 pr = {__builtin_amdgcn_exp2f(__builtin_fmaf(s[base + 2 * y], c2, -shift)),
-                      __builtin_amdgcn_exp2f(__builtin_fmaf(s[base + 2 * y + 1], c2, -shift))};
-        const bf16x2 t2 = __builtin_convertvector(pr, bf16x2);
-        rsum = __builtin_amdgcn_fdot2_f32_bf16(t2, ones, rsum, false);
-        pk[2 * y] = t2[0];
-        pk[2 * y + 1] = t2[1];
-    }
-    return pk;
-}
-
-// n x { one MFMA, ds LDS reads, v vector-ALU instructions }: the order the scheduler is asked to emit
-template <int N, int DS, int V>
-__device__ __forceinline__ void interleave()
-{
-#pragma unroll
-    for (int i = 0; i < N; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        if (DS) __builtin_amdgcn_sched_group_barrier(0x100, DS, 0);
-        if (V) __builtin_amdgcn_sched_group_barrier(0x002, V, 0);
-    }
-}
 
 __device__ __forceinline__ void load_kf(bf16x8 (&kf)[8], const Stage &sg, int ln, int lh)
 {
@@ -197,22 +204,11 @@ __device__ __forceinline__ void s_mfma(floatx16 (&s)[2], const bf16x8 (&kf)[8], 
 // two probabilities: exp2(s * c2 - shift), packed; rsum += the rounded values
 __device__ __forceinline__ bf16x2 exp2_pack2(float s0, float s1, float c2, float shift, float &rsum)
 {
-    const bf16x2 ones = {(bf16_t)1.0f, (bf16_t)1.0f};
     floatx2 pr = {__builtin_amdgcn_exp2f(__builtin_fmaf(s0, c2, -shift)), __builtin_amdgcn_exp2f(__builtin_fmaf(s1, c2, -shift))};
     const bf16x2 t2 = __builtin_convertvector(pr, bf16x2);
+    const bf16x2 ones = {(bf16_t)1.0f, (bf16_t)1.0f};
     rsum = __builtin_amdgcn_fdot2_f32_bf16(t2, ones, rsum, false);
     return t2;
-}
-
-// O^T += V'^T P^T for one query tile
-template <int NT>
-__device__ __forceinline__ void pv_mfma(State &st, const bf16x8 (&vf)[8], const bf16x8 (&pf)[2])
-{
-#pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-        for (int k2 = 0; k2 < 2; ++k2)
-            st.acc_o[dt][NT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[2 * dt + k2], pf[k2], st.acc_o[dt][NT], 0, 0, 0);
 }
 
 // What a sub-tile that is not plain needs before the softmax of one query tile: the token-level mask (masked scores
@@ -255,7 +251,7 @@ template <int P>
 __device__ __forceinline__ void step(State &st, floatx16 (&s_cur)[2], floatx16 (&s_nxt)[2], bf16x8 (&kf)[8],
                                      const bf16x8 (&qf)[2][8], Stage &sg_v, const Stage &sg_k, const int (&qpos)[2],
                                      int room, bool masked, float c2, int ln, int lh, const TileBuffers &buf,
-                                     const LaneOffsets &off, int j_load, int wave)
+                                     const LaneOffsets &off, int j_load, int wave, int lane)
 {
     bf16x8 vf[8], pf[2][2];
     if (masked || !__all(st.seen[0] && st.seen[1])) {
@@ -285,20 +281,55 @@ __device__ __forceinline__ void step(State &st, floatx16 (&s_cur)[2], floatx16 (
 #undef PBS_X_STEP
     st.l[0] += rsum0;
     st.bad = st.bad || !(rsum0 <= kBigRowSum);
-    // ---- Y
-    load_kf(kf, sg_k, ln, lh);
-    pv_mfma<0>(st, vf, pf[0]);
+    // ---- Y: O^T update of tile 0 || softmax of tile 1 || K' fragments of the sub-tile after the next
     float rsum1 = 0.0f;
-    pf[1][0] = exp2_pack8(s_cur[1], 0, c2, st.mref[1], rsum1);
-    pf[1][1] = exp2_pack8(s_cur[1], 8, c2, st.mref[1], rsum1);
+    const unsigned char *kl = sg_k.k + ln * kKRowB + lh * 16;
+    // MFMA i of a group works on fragment PBS_MQ(i): the four O^T tiles with the first 16 keys, then with the other
+    // 16, so that consecutive MFMAs never share an accumulator
+#define PBS_MQ(i) ((((i) & 3) << 1) | ((i) >> 2))
+#define PBS_Y_STEP(q)                                                                                        \
+    {                                                                                                        \
+        st.acc_o[PBS_MQ(q) >> 1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                               \
+            vf[PBS_MQ(q)], pf[0][PBS_MQ(q) & 1], st.acc_o[PBS_MQ(q) >> 1][0], 0, 0, 0);                      \
+        kf[q] = *reinterpret_cast<const bf16x8 *>(kl + (q) * 32);                                            \
+        const bf16x2 t2 = exp2_pack2(s_cur[1][2 * (q)], s_cur[1][2 * (q) + 1], c2, st.mref[1], rsum1);       \
+        pf[1][(q) >> 2][2 * ((q) & 3)] = t2[0];                                                              \
+        pf[1][(q) >> 2][2 * ((q) & 3) + 1] = t2[1];                                                          \
+        __builtin_amdgcn_sched_barrier(0);                                                                   \
+    }
+    PBS_Y_STEP(0) PBS_Y_STEP(1) PBS_Y_STEP(2) PBS_Y_STEP(3) PBS_Y_STEP(4) PBS_Y_STEP(5) PBS_Y_STEP(6) PBS_Y_STEP(7)
+#undef PBS_Y_STEP
     st.l[1] += rsum1;
     st.bad = st.bad || !(rsum1 <= kBigRowSum);
-    interleave<8, 1, 8>();
+    // ---- Z: O^T update of tile 1.  Two MFMAs are queued before the barrier, so the matrix pipe has work while the
+    // waves meet; after the barrier every wave is done reading stage sg_v, which is refilled under the rest.
+#define PBS_Z_MFMA(i)                                                                                        \
+    st.acc_o[PBS_MQ(i) >> 1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                                   \
+        vf[PBS_MQ(i)], pf[1][PBS_MQ(i) & 1], st.acc_o[PBS_MQ(i) >> 1][1], 0, 0, 0);
+    PBS_Z_MFMA(0) PBS_Z_MFMA(1)
     __builtin_amdgcn_sched_barrier(0);
-    // ---- every wave is done reading stage sg_v: refill it, under the MFMAs of group Z
     sync_stages();
-    issue_stage<P>(sg_v, buf, off, j_load, wave);
-    pv_mfma<1>(st, vf, pf[1]);
+    const StageLoad ld = stage_load<P>(sg_v, buf, j_load, wave);
+    issue_load<0>(ld, buf, off); issue_load<1>(ld, buf, off);
+    __builtin_amdgcn_sched_barrier(0);
+    PBS_Z_MFMA(2)
+    issue_load<2>(ld, buf, off); issue_load<3>(ld, buf, off);
+    __builtin_amdgcn_sched_barrier(0);
+    PBS_Z_MFMA(3)
+    issue_load<4>(ld, buf, off); issue_load<5>(ld, buf, off);
+    __builtin_amdgcn_sched_barrier(0);
+    PBS_Z_MFMA(4)
+    issue_load<6>(ld, buf, off); issue_load<7>(ld, buf, off);
+    __builtin_amdgcn_sched_barrier(0);
+    PBS_Z_MFMA(5)
+    issue_load<8>(ld, buf, off); issue_load<9>(ld, buf, off);
+    __builtin_amdgcn_sched_barrier(0);
+    PBS_Z_MFMA(6)
+    issue_positions(sg_v, ld, buf, wave, lane);
+    __builtin_amdgcn_sched_barrier(0);
+    PBS_Z_MFMA(7)
+#undef PBS_Z_MFMA
+#undef PBS_MQ
     __builtin_amdgcn_sched_barrier(0);
 }
 
@@ -383,10 +414,10 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         // prologue: the four parts of the first block, its first scores, the K' fragments of part 1
         int jraw = entry(0);
         int jc = jraw < 0 ? 0 : jraw;
-        issue_stage<0>(sg0, buf, off, jc, wave);
-        issue_stage<1>(sg1, buf, off, jc, wave);
-        issue_stage<2>(sg2, buf, off, jc, wave);
-        issue_stage<3>(sg3, buf, off, jc, wave);
+        issue_stage<0>(sg0, buf, off, jc, wave, lane);
+        issue_stage<1>(sg1, buf, off, jc, wave, lane);
+        issue_stage<2>(sg2, buf, off, jc, wave, lane);
+        issue_stage<3>(sg3, buf, off, jc, wave, lane);
         sync_stages();
         floatx16 sa[2], sb[2];
         bf16x8 kf[8];
@@ -404,10 +435,10 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
             const int room0 = jraw < 0 ? 0 : g.n - jraw * BLOCK;   // keys of the block that exist
             // part p: softmax and O^T update of part p; scores of part p + 1; K' fragments of part p + 2 (parts past
             // 3 are those of the next block); part p of the next block is loaded into the stage part p leaves
-            step<0>(st, sa, sb, kf, qf, sg0, sg2, qpos, room0, masked, c2, ln, lh, buf, off, jn, wave);
-            step<1>(st, sb, sa, kf, qf, sg1, sg3, qpos, room0 - KS, masked, c2, ln, lh, buf, off, jn, wave);
-            step<2>(st, sa, sb, kf, qf, sg2, sg0, qpos, room0 - 2 * KS, masked, c2, ln, lh, buf, off, jn, wave);
-            step<3>(st, sb, sa, kf, qf, sg3, sg1, qpos, room0 - 3 * KS, masked, c2, ln, lh, buf, off, jn, wave);
+            step<0>(st, sa, sb, kf, qf, sg0, sg2, qpos, room0, masked, c2, ln, lh, buf, off, jn, wave, lane);
+            step<1>(st, sb, sa, kf, qf, sg1, sg3, qpos, room0 - KS, masked, c2, ln, lh, buf, off, jn, wave, lane);
+            step<2>(st, sa, sb, kf, qf, sg2, sg0, qpos, room0 - 2 * KS, masked, c2, ln, lh, buf, off, jn, wave, lane);
+            step<3>(st, sb, sa, kf, qf, sg3, sg1, qpos, room0 - 3 * KS, masked, c2, ln, lh, buf, off, jn, wave, lane);
             jraw = jnraw;
             jc = jn;
         }
