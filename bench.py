@@ -23,7 +23,7 @@ sys.path.insert(0, ROOT)
 MFMA_BF16_PEAK_TFLOPS = 2500.0       # MI355X dense bf16 matrix peak
 # HBM bytes per pbs_attn_fwd launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same counters
 # read for a plain 1 GiB copy (profiles/bench_c3_hbm_traffic.md); only known for the workloads listed here.
-ATTN_TRAFFIC_BYTES = {"c3": 17393300 * 2.0 * 1024 * (1048576 / 524346 / 2.0) + 1048580 * 1024.0}
+ATTN_TRAFFIC_BYTES = {"c3": 12910900 * 2.0 * 1024 * (1048576 / 524327 / 2.0) + 1049090 * 1024.0}
 HBM_PEAK_GBS = 8000.0                # MI355X HBM3E
 
 
@@ -140,7 +140,7 @@ def main():
             pbs.segment_permute(p, None, K, V, pipe.kidx, pipe.Kp, pipe.Vt)
             mark(2)
             mark(3)
-            pbs.attn_fwd(p, Q, pipe.Kp, pipe.Vt, None, pipe.kidx, row_cnt, col_idx, pipe.Op)
+            pbs.attn_fwd(p, Q, pipe.Kp, pipe.Vt, None, pipe.kidx, row_cnt, col_idx, pipe.Op, ws=pipe.ws4)
         else:
             pbs.key_scores(p, Q, K, pipe.scores, pipe.ws1)
             mark(1)
@@ -148,7 +148,7 @@ def main():
             mark(2)
             pbs.block_mask(p, Q, pipe.Kp, pipe.mask_bits, pipe.row_cnt, pipe.col_idx, pipe.ws3)
             mark(3)
-            pbs.attn_fwd(p, Q, pipe.Kp, pipe.Vt, None, pipe.kidx, pipe.row_cnt, pipe.col_idx, pipe.Op)
+            pbs.attn_fwd(p, Q, pipe.Kp, pipe.Vt, None, pipe.kidx, pipe.row_cnt, pipe.col_idx, pipe.Op, ws=pipe.ws4)
         mark(4)
         pbs.unpermute(p, pipe.Op, None, pipe.O)        # P_sigma = I in the paper's main setting: nothing to move
         mark(5)

@@ -153,6 +153,13 @@ pbs_status pbs_block_mask(const pbs_problem *p, const void *Qp, const void *Kp, 
  *   kidx [batch,h_kv,n]; row_cnt, col_idx as written by pbs_block_mask (any order of the listed blocks is
  *   accepted); Op [batch,h_q,n,d] written; lse [batch,h_q,n] float32 or NULL: log-sum-exp of the visible,
  *   listed logits of every query row.
+ *   ws: pbs_workspace_bytes(p, PBS_STAGE_ATTN_FWD) bytes, 256-byte aligned device memory (0 bytes, and ws may be NULL,
+ *   unless dtype is bf16 with d = 128 and block = 128).  For that shape the call launches two kernels on the stream:
+ *   one that keeps a fixed softmax reference per query and writes one int32 flag per query block into ws (1 = some
+ *   probability outgrew the reference by more than 2^64), and one that recomputes the flagged query blocks with the
+ *   running-maximum recurrence of Algorithm 1.  The contents of ws need not be initialised and mean nothing afterwards.
+ *   Setting the environment variable PBS_ATTN_NARROW (read once per process) sends every query block of that shape
+ *   through the second kernel alone; it exists for A/B timing.
  */
 pbs_status pbs_attn_fwd(const pbs_problem *p, const void *Qp, const void *Kp, const void *Vt,
                         const int32_t *qidx, const int32_t *kidx, const int32_t *row_cnt, const int32_t *col_idx,

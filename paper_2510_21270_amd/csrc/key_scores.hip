@@ -100,7 +100,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     bf16x8 kf[8], kn[8];                                     // current fragments and the prefetched next tile
     load_kfrags(kf, Kh, min(wg * kKeysPerWg + wave * 32, g.n - 1), g.n, lane);
     for (int key0 = wg * kKeysPerWg + wave * 32; key0 < key_end; key0 += 4 * 32) {
-        load_kfrags(kn, Kh, min(key0 + 4 * 32, g.n - 1), g.n, lane);
+        load_kfrags(kn, Kh, key0 + 4 * 32 < key_end ? key0 + 4 * 32 : key0, g.n, lane);   // last tile: a cached re-read
 #pragma unroll
         for (int nt = 0; nt < 4; ++nt) {
             asm volatile("" ::: "memory");                   // keeps the Qhat fragment reads inside the loop
@@ -208,7 +208,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     bf16x8 kf[8], kn[8];
     load_kfrags(kf, Kh, min(wg * kKeysPerWg + wave * 32, g.n - 1), g.n, lane);
     for (int key0 = wg * kKeysPerWg + wave * 32; key0 < key_end; key0 += 4 * 32) {
-        load_kfrags(kn, Kh, min(key0 + 4 * 32, g.n - 1), g.n, lane);
+        load_kfrags(kn, Kh, key0 + 4 * 32 < key_end ? key0 + 4 * 32 : key0, g.n, lane);   // last tile: a cached re-read
         float sum = 0.0f;
 #pragma unroll
         for (int mt = 0; mt < 4; ++mt) {

@@ -82,6 +82,8 @@ def test_null_pointers_are_rejected_before_any_launch(lib):
     assert lib.pbs_key_scores(ref, fake, fake, fake, fake, 16, None) == 4
     assert lib.pbs_key_scores(ref, fake, fake, fake, ctypes.c_void_p(4096 + 8), 1 << 30, None) == 4
     assert lib.pbs_block_mask(ref, fake, fake, fake, fake, fake, fake, 16, None) == 4
+    assert lib.pbs_attn_fwd(ref, fake, fake, fake, None, fake, fake, fake, fake, None, None, 0, None) == 1
+    assert lib.pbs_attn_fwd(ref, fake, fake, fake, None, fake, fake, fake, fake, None, fake, 16, None) == 4
     # misaligned tensors
     assert lib.pbs_unpermute(ref, ctypes.c_void_p(4096 + 4), None, fake, None) == 2
     # invalid problem wins over everything

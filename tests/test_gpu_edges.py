@@ -152,3 +152,35 @@ def test_reversed_keys_rows_see_nothing_in_early_blocks(oracle):
                        i32_dev(kidx), i32_dev(row_cnt), i32_dev(col_idx))
     torch.cuda.synchronize()
     check_close(to_host(got), oracle.dense_causal(Q, K, V), "bf16", "reversed")
+
+
+def test_scores_climbing_far_above_the_first_keys_take_the_second_pass(oracle):
+    # The 64-queries-per-wave kernel fixes a query's softmax reference at its first visible keys and flags query
+    # blocks whose probabilities outgrow it by more than 2^64; the library must then recompute those blocks with the
+    # rescaling kernel.  Keys are built so that the logits rise by about 0.12 nats per key along the sequence:
+    # every query block but the first meets keys many times 44 nats above their first sub-tile.
+    n, block, d, Hq, Hkv = 1024, 128, 128, 2, 1
+    rng = np.random.default_rng(17)
+    u = np.zeros(d, dtype=np.float32)
+    u[:4] = 1.0
+    Q = np.tile(u * 4.0, (1, Hq, n, 1)).astype(np.float32)                       # q . u = 16 for every query
+    ramp = (np.arange(n, dtype=np.float32) * 0.35)[None, None, :, None]        # logit = 16 * ramp * u.u/4 / sqrt(d)
+    K = wl.round_to_bf16(ramp * (u / 4.0)[None, None, None, :] + 0.01 * rng.standard_normal((1, Hkv, n, d)).astype(np.float32))
+    Q = wl.round_to_bf16(Q + 0.01 * rng.standard_normal(Q.shape).astype(np.float32))
+    V = wl.round_to_bf16(rng.standard_normal((1, Hkv, n, d)).astype(np.float32))
+    T = n // block
+    kidx = np.tile(np.arange(n, dtype=np.int32), (1, Hkv, 1))
+    row_cnt = np.tile(np.arange(1, T + 1, dtype=np.int32), (1, Hq, 1))
+    col_idx = np.tile(np.arange(T, dtype=np.int32), (1, Hq, T, 1))
+    p = pbs.problem(1, Hq, Hkv, n, d, block, block, "bf16")
+    logit_span = float((Q[0, 0, -1] @ K[0, 0, -1] - Q[0, 0, -1] @ K[0, 0, 0]) / np.sqrt(d))
+    assert logit_span > 100.0                                                    # far beyond 2^64 = e^44
+    ws = pbs.alloc_workspace(p, pbs.STAGE_ATTN_FWD)
+    got, lse = pbs.attn_fwd(p, to_dev(Q, "bf16"), to_dev(K, "bf16"), to_dev(vt_layout(V, block), "bf16"), None,
+                            i32_dev(kidx), i32_dev(row_cnt), i32_dev(col_idx), want_lse=True, ws=ws)
+    torch.cuda.synchronize()
+    flags = ws[:Hq * T * 4].view(torch.int32).cpu().numpy()
+    assert flags.sum() >= Hq * (T - 3), "the first pass was expected to flag the long query blocks"
+    want, want_lse = oracle.attn_fwd(Q, K, V, None, kidx, row_cnt, col_idx, block, want_lse=True)
+    check_close(to_host(got), want, "bf16", "second pass")
+    np.testing.assert_allclose(lse.cpu().numpy(), want_lse, atol=2e-2, rtol=2e-4)
