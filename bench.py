@@ -33,6 +33,8 @@ def make_workload(name):
         return wl.c3_llama128k()
     if name == "c2":
         return wl.c2_llama()
+    if name == "c3s":                                    # extra: config 3 with keys that really are heavy
+        return wl.c3_strong()
     if name == "c4":
         return wl.c4_qwen()
     if name == "c1":
@@ -104,6 +106,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="c3")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
+    ap.add_argument("--no-permute", action="store_true",
+                    help="keep the keys in token order (identity permutation): what Algorithm 2 selects, and what "
+                         "the attention costs, without the paper's permutation")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="after the timed region, run one plain device copy of known size through pbs_unpermute, so "
                          "that a rocprofv3 --pmc run of this command shows what FETCH_SIZE / WRITE_SIZE read for it")
@@ -144,7 +149,7 @@ def main():
         else:
             pbs.key_scores(p, Q, K, pipe.scores, pipe.ws1)
             mark(1)
-            pbs.segment_permute(p, pipe.scores, K, V, pipe.kidx, pipe.Kp, pipe.Vt)
+            pbs.segment_permute(p, None if args.no_permute else pipe.scores, K, V, pipe.kidx, pipe.Kp, pipe.Vt)
             mark(2)
             pbs.block_mask(p, Q, pipe.Kp, pipe.mask_bits, pipe.row_cnt, pipe.col_idx, pipe.ws3)
             mark(3)
@@ -174,6 +179,43 @@ def main():
               (scratch.numel() * scratch.element_size(), scratch.numel() * scratch.element_size()), file=sys.stderr)
         del scratch
 
+    # ---- untimed extras: where the planted keys end up, the inverse permutation with a real sigma, a plain copy
+    extras = {}
+    if not given and "planted" in w.extra:
+        kidx_h = pipe.kidx.cpu().numpy()
+        seg = w.segment
+        ranks = []
+        for (b, h), pos in w.extra["planted"].items():
+            slot_of = np.empty(w.n, dtype=np.int64)
+            slot_of[kidx_h[b, h]] = np.arange(w.n)
+            pos = pos[pos < (w.n // seg) * seg]
+            ranks.append((slot_of[pos] % seg) / float(seg))
+        ranks = np.concatenate(ranks) if ranks else np.zeros(0)
+        if ranks.size:                                     # 0 = first slot of its segment, 0.5 = no better than chance
+            extras["planted_keys_mean_rank_in_segment"] = float(ranks.mean())
+            extras["planted_keys_in_first_block_of_segment"] = float((ranks < w.block / float(seg)).mean())
+    def timed(fn, reps=3):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+    if not args.copy_calibration:
+        from paper_2510_21270_amd import workloads as wl
+        scratch = torch.empty_like(pipe.Op)
+        nbytes = 2.0 * scratch.numel() * scratch.element_size()
+        ms_copy = timed(lambda: pbs.unpermute(p, pipe.Op, None, scratch))
+        sigma = torch.from_numpy(wl.random_segment_perm(7, w.batch * w.h_q, w.n, w.segment)
+                                 .reshape(w.batch, w.h_q, w.n)).cuda()
+        ms_sigma = timed(lambda: pbs.unpermute(p, pipe.Op, sigma, scratch))
+        extras["plain_copy"] = {"ms": ms_copy, "GBps": nbytes / ms_copy / 1e6, "bytes": nbytes}
+        extras["unpermute_random_sigma"] = {"ms": ms_sigma, "GBps": (nbytes + sigma.numel() * 4) / ms_sigma / 1e6}
+        del scratch, sigma
+
     cnt = (row_cnt if given else pipe.row_cnt).cpu().numpy().astype(np.int64)
     visited = int(cnt.sum())
     T = w.T
@@ -196,14 +238,15 @@ def main():
         "ms_per_layer": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
         "config": dict(w.describe(), visited_blocks=visited, causal_blocks=causal_total,
-                       density_vs_causal=visited / causal_total, given_mask=bool(given)),
+                       density_vs_causal=visited / causal_total, given_mask=bool(given),
+                       permuted=not (given or args.no_permute)),
         "stages_ms": stage_ms,
         "stages_gbs": {k: alg_bytes[k] / (stage_ms[k] * 1e-3) / 1e9 for k in alg_bytes if stage_ms[k] > 0},
         "roofline": {"kernel": "pbs_attn_fwd", "bound": "mfma", "achieved": attn_tflops,
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": attn_tflops / MFMA_BF16_PEAK_TFLOPS,
                      "traffic": ATTN_TRAFFIC_BYTES.get(args.workload), "avg_launch_ms": stage_ms["attn_fwd"]},
         "context": {"paper_h100_128k_ms": {"flashattention": 443.29, "pbs_total": 159.87, "speedup": 2.77},
-                    "input_generation_s": t_gen},
+                    "input_generation_s": t_gen, **extras},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w)

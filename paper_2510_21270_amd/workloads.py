@@ -121,14 +121,22 @@ def _finish(name, Q, K, V, dtype, **kw):
 
 
 def planted(name, seed, h_q, h_kv, n, d, block, segment, tau, dtype, n_scatter, rope_base=None, bursts=0,
-            burst_len=0, batch=1, flags=1):
-    """The family behind configs 1-4: Gaussian Q/K/V, optional RoPE on Q/K, planted heavy hitters + 4 sinks."""
+            burst_len=0, batch=1, flags=1, shared_query=0.0):
+    """The family behind configs 1-4: Gaussian Q/K/V, optional RoPE on Q/K, planted heavy hitters + 4 sinks.
+    shared_query > 0 (not part of any numbered config) adds that multiple of one seeded unit vector per kv head to
+    every query of its group, so that the mean-query direction the planted keys point along is one all queries share."""
     Q = _normal(seed, 1, (batch, h_q, n, d))
     K = _normal(seed, 2, (batch, h_kv, n, d))
     V = _normal(seed, 3, (batch, h_kv, n, d))
     if rope_base is not None:
         _rope_inplace(Q, rope_base)
         _rope_inplace(K, rope_base)
+    if shared_query > 0.0:
+        r = h_q // h_kv
+        for b in range(batch):
+            for h in range(h_kv):
+                u0 = _rng(seed, 200 + b * h_kv + h).standard_normal(d).astype(np.float32)
+                Q[b, h * r:(h + 1) * r] += np.float32(shared_query) * (u0 / np.linalg.norm(u0))
     pl = _plant(Q, K, seed, n_scatter, bursts=bursts, burst_len=burst_len)
     return _finish(name, Q, K, V, dtype, block=block, segment=segment, tau=tau, flags=flags,
                    extra={"planted": pl, "seed": seed})
@@ -149,6 +157,15 @@ def c3_llama128k(n=131072, h_q=32, h_kv=8, seed=SEEDS["c3"]):
     """Config 3: the headline point, same layer at N=131072 with 256 heavy hitters per kv head."""
     ns = max(1, 256 * n // 131072)
     return planted("c3_llama_bf16_n%d" % n, seed, h_q, h_kv, n, 128, 128, 1024, 0.9, "bf16", ns, rope_base=5e5)
+
+
+def c3_strong(n=131072, h_q=32, h_kv=8, seed=SEEDS["c3"]):
+    """NOT one of the numbered configs: an extra, strengthened variant of config 3 in which the planted keys really
+    are heavy hitters.  Every query carries a shared component of 24 along its kv head's direction (a planted key
+    4u then has logit ~ 8.5 nats against every query, the Gaussian keys ~ N(0, 2.3^2)), and one key in eight is
+    planted, so that after the segmented permutation the first block of each 1024-key segment is all heavy."""
+    return planted("c3_strong_bf16_n%d" % n, seed, h_q, h_kv, n, 128, 128, 1024, 0.9, "bf16", n // 8, rope_base=5e5,
+                   shared_query=24.0)
 
 
 def c4_qwen(n=65536, h_q=28, h_kv=4, seed=SEEDS["c4"]):
