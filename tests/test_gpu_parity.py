@@ -32,10 +32,13 @@ def _case(name):
         return wl.planted("bf16_d64", 14, 4, 4, 530, 64, 16, 128, 0.9, "bf16", 4)
     if name == "f32_b128":
         return wl.planted("f32_b128", 15, 2, 2, 700, 64, 128, 256, 0.9, "f32", 4)
+    if name == "bf16_r7":                                                       # Qwen-like GQA 7:1, bursts, ragged
+        return wl.planted("bf16_r7", 16, 7, 1, 1536 + 19, 128, 128, 512, 0.95, "bf16", 8, rope_base=1e6, bursts=2,
+                          burst_len=16)
     raise KeyError(name)
 
 
-CASES = ["c1", "bf16_b128", "bf16_b64", "f32_d128", "bf16_d64", "f32_b128"]
+CASES = ["c1", "bf16_b128", "bf16_b64", "f32_d128", "bf16_d64", "f32_b128", "bf16_r7"]
 _cache = {}
 
 
