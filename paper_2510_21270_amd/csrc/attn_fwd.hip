@@ -1,7 +1,9 @@
 // pbs_attn_fwd: Algorithm 1's main loop -- online-softmax attention over the listed key blocks only.
+// This file holds the entry point, the 32-queries-per-wave matrix-core kernel and the vector kernel; the
+// 64-queries-per-wave kernel that serves block = 128 first is in attn_wide.hip.
 //
-// Matrix-core kernel (bf16, d = 128, block 64 or 128).  Everything is kept TRANSPOSED so that one lane owns
-// one query for the whole row of work:
+// Matrix-core kernel (bf16, d = 128; block 64, and the second pass of block 128).  Everything is kept TRANSPOSED so
+// that one lane owns one query for the whole row of work:
 //     S^T = K'_j Q'_i^T      A = K' tile rows (from LDS), B = Q' fragments (registers, loaded once)
 //     O^T += V'_j^T P^T      A = V'^T tile rows (from LDS; V' is stored block-transposed in HBM), B = P^T
 // With v_mfma_f32_32x32x16_bf16 the accumulator of S^T gives lane (n, h) the scores of query n against 16 keys
@@ -9,7 +11,7 @@
 // cross-lane traffic for P, and the running max / sum / rescale of a query are lane-local (one xor-32
 // exchange).  The K' tile is stored in LDS with bits 2 and 3 of the row index swapped so that the 8 values a
 // lane contributes to one 16-key contraction step are 8 CONSECUTIVE keys, which lets V'^T be read from LDS
-// with plain 16-byte loads.  LDS tiles are XOR-swizzled in 16-byte chunks against bank conflicts.
+// with plain 16-byte loads.  LDS tile rows are padded by 16 bytes against bank conflicts.
 // A block that is not listed costs nothing: the loop runs over the list.
 //
 // Vector kernel (fp32 arithmetic): every other supported dtype / d / block.

@@ -1,5 +1,5 @@
-"""GPU parity at the FULL sizes of configs 2 and 3 (Llama-3.1-8B-shaped layer, N = 32768 and N = 131072), in the
-launch configuration bench.py times (the same binding calls on the same preallocated Pipeline buffers).
+"""GPU parity at the FULL sizes of configs 2, 3 (Llama-3.1-8B-shaped layer, N = 32768 and N = 131072), 4 (Qwen2.5-7B-
+shaped, N = 65536, GQA 7:1) and 5 (caller-supplied lists at N = 65536), in the launch configuration bench.py times (the same binding calls on the same preallocated Pipeline buffers).
 
 Discrete outputs (permutation indices, permuted tensors, block masks, block lists) are compared in full and must be
 bit-exact.  The attention output is compared on SAMPLED query blocks that the oracle computes one by one: first
@@ -24,7 +24,7 @@ def _setup(name, oracle):
         return _state[name]
     _state.clear()                                   # one full-size workload in memory at a time
     torch.cuda.empty_cache()
-    w = wl.c2_llama() if name == "c2" else wl.c3_llama128k()
+    w = {"c2": wl.c2_llama, "c3": wl.c3_llama128k, "c4": wl.c4_qwen}[name]()
     s = oracle.key_scores(w.Q, w.K, w.block)
     s_h = s.astype(np.float32)
     kidx = oracle.segment_argsort(s_h, w.segment)
@@ -37,7 +37,7 @@ def _setup(name, oracle):
     return st
 
 
-@pytest.mark.parametrize("name", ["c2", "c3"])
+@pytest.mark.parametrize("name", ["c2", "c4", "c3"])
 def test_full_size_scores_permutation_and_mask(oracle, name):
     st = _setup(name, oracle)
     w, p, pipe = st["w"], st["p"], st["pipe"]
@@ -67,7 +67,7 @@ def test_full_size_scores_permutation_and_mask(oracle, name):
     assert int(st["row_cnt"].max()) <= w.T and int(st["row_cnt"].sum()) <= w.h_q * (R * R * G * (G + 1) // 2)
 
 
-@pytest.mark.parametrize("name", ["c2", "c3"])
+@pytest.mark.parametrize("name", ["c2", "c4", "c3"])
 def test_full_size_attention_on_sampled_rows(oracle, name):
     st = _setup(name, oracle)
     w, p, pipe = st["w"], st["p"], st["pipe"]
@@ -92,3 +92,29 @@ def test_full_size_attention_on_sampled_rows(oracle, name):
     vmax = st["V"].float().abs().amax(dim=2)                 # [1,Hkv,d]
     bound = vmax.repeat_interleave(w.h_q // w.h_kv, dim=1)[:, :, None, :] * 1.01 + 1e-3
     assert (Op.float().abs() <= bound).all()
+
+
+@pytest.mark.parametrize("rho", [0.10, 1.0])
+def test_full_size_given_lists_on_sampled_rows(oracle, rho):
+    """Config 5: identity key order, seeded block lists of density rho at N = 65536, attention only."""
+    _state.clear()
+    torch.cuda.empty_cache()
+    w = wl.c5_density(rho)
+    p = make_problem(w)
+    T = w.T
+    row_cnt, col_idx = w.extra["row_cnt"], w.extra["col_idx"]
+    assert int(row_cnt.sum()) == w.h_q * (T * (T + 1) // 2 if rho >= 1.0 else int(round(rho * (T * (T + 1) // 2))))
+    Q, K, V = to_dev(w.Q, "bf16"), to_dev(w.K, "bf16"), to_dev(w.V, "bf16")
+    kidx, Kp, Vt = pbs.segment_permute(p, None, K, V)
+    assert torch.equal(Kp, K) and torch.equal(kidx[0, 0].cpu(), torch.arange(w.n, dtype=torch.int32))
+    Op, lse = pbs.attn_fwd(p, Q, Kp, Vt, None, kidx, i32_dev(row_cnt), i32_dev(col_idx), want_lse=True)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(9)
+    rows = [[0, int(rng.integers(0, w.h_q)), int(i)] for i in [0, 1, T // 3, T - 2, T - 1] + rng.integers(0, T, size=5).tolist()]
+    kid = np.tile(np.arange(w.n, dtype=np.int32), (1, w.h_kv, 1))
+    want, want_lse = oracle.attn_rows(w.Q, w.K, w.V, None, kid, row_cnt, col_idx, w.block, rows, want_lse=True)
+    for u, (b, h, i) in enumerate(rows):
+        sl = slice(i * w.block, (i + 1) * w.block)
+        check_close(to_host(Op[b, h, sl]), want[u], "bf16", "c5 rho=%g row (%d,%d,%d)" % (rho, b, h, i))
+        np.testing.assert_allclose(lse[b, h, sl].cpu().numpy(), want_lse[u], rtol=0, atol=2e-2)
+    assert torch.isfinite(Op).all()
