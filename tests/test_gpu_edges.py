@@ -184,3 +184,32 @@ def test_scores_climbing_far_above_the_first_keys_take_the_second_pass(oracle):
     want, want_lse = oracle.attn_fwd(Q, K, V, None, kidx, row_cnt, col_idx, block, want_lse=True)
     check_close(to_host(got), want, "bf16", "second pass")
     np.testing.assert_allclose(lse.cpu().numpy(), want_lse, atol=2e-2, rtol=2e-4)
+
+
+def test_rescaling_kernel_alone_serves_block_128(oracle):
+    # PBS_ATTN_NARROW (read once per process) sends block 128 through the 32-queries-per-wave kernel only; run the
+    # same comparison as the parity test in a child process with the variable set.
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    code = r"""
+import sys
+sys.path.insert(0, %r); sys.path.insert(0, %r)
+import numpy as np, torch
+from gpu_helpers import check_close, i32_dev, make_problem, to_dev, to_host, vt_layout
+from oracle import pbs_oracle as oracle
+from paper_2510_21270_amd import binding as pbs, workloads as wl
+w = wl.planted("narrow", 21, 4, 2, 2048 + 31, 128, 128, 512, 0.9, "bf16", 8, rope_base=5e5)
+res = oracle.pipeline(w.Q, w.K, w.V, w.block, w.segment, w.tau, flags=w.flags)
+p = make_problem(w)
+Op, lse = pbs.attn_fwd(p, to_dev(res["Qp"], "bf16"), to_dev(res["Kp"], "bf16"), to_dev(vt_layout(res["Vp"], w.block), "bf16"),
+                       None, i32_dev(res["kidx"]), i32_dev(res["row_cnt"]), i32_dev(res["col_idx"]), want_lse=True)
+torch.cuda.synchronize()
+check_close(to_host(Op), res["Op"], "bf16", "narrow only")
+np.testing.assert_allclose(lse.cpu().numpy(), res["lse"], atol=2e-2, rtol=0)
+print("narrow-only ok")
+""" % (root, os.path.join(root, "tests"))
+    env = dict(os.environ, PBS_ATTN_NARROW="1")
+    out = subprocess.run([sys.executable, "-c", code], env=env, capture_output=True, text=True, timeout=240)
+    assert out.returncode == 0 and "narrow-only ok" in out.stdout, out.stdout + out.stderr
