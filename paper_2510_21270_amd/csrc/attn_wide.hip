@@ -261,8 +261,19 @@ __device__ __forceinline__ void step(State &st, floatx16 (&s_cur)[2], floatx16 (
     }
     __builtin_amdgcn_sched_barrier(0);
     // ---- X (the score MFMAs are opaque statements, so the interleaving with the softmax of tile 0 is written out)
-    load_vf(vf, sg_v, ln, lh);
+    const unsigned char *vl = sg_v.v + ln * kVRowB + lh * 16;
     float rsum0 = 0.0f;
+    // The exponentials of pair x are issued in slot x, their pack and row sum in slot x + 1, so that no instruction
+    // waits on the result of the one just before it.
+    floatx2 pr0 = {0.0f, 0.0f}, ar0 = {0.0f, 0.0f};
+#define PBS_PACK0(x)                                                                                         \
+    {                                                                                                        \
+        const bf16x2 t2 = __builtin_convertvector(pr0, bf16x2);                                              \
+        const bf16x2 ones = {(bf16_t)1.0f, (bf16_t)1.0f};                                                    \
+        rsum0 = __builtin_amdgcn_fdot2_f32_bf16(t2, ones, rsum0, false);                                     \
+        pf[0][(x) >> 2][2 * ((x) & 3)] = t2[0];                                                              \
+        pf[0][(x) >> 2][2 * ((x) & 3) + 1] = t2[1];                                                          \
+    }
 #define PBS_X_STEP(x)                                                                                        \
     {                                                                                                        \
         if ((x) == 0) {                                                                                      \
@@ -272,12 +283,23 @@ __device__ __forceinline__ void step(State &st, floatx16 (&s_cur)[2], floatx16 (
             s_mfma_next<0>(s_nxt[0], kf[x], qf[0][x]);                                                       \
             s_mfma_next<1>(s_nxt[1], kf[x], qf[1][x]);                                                       \
         }                                                                                                    \
-        const bf16x2 t2 = exp2_pack2(s_cur[0][2 * (x)], s_cur[0][2 * (x) + 1], c2, st.mref[0], rsum0);       \
-        pf[0][(x) >> 2][2 * ((x) & 3)] = t2[0];                                                              \
-        pf[0][(x) >> 2][2 * ((x) & 3) + 1] = t2[1];                                                          \
+        vf[x] = *reinterpret_cast<const bf16x8 *>(vl + ((x) >> 1) * 32 * kVRowB + ((x) & 1) * 32);           \
+        if ((x) > 1) PBS_PACK0((x) - 2)                                                                      \
+        if ((x) > 0) {                                                                                       \
+            pr0[0] = __builtin_amdgcn_exp2f(ar0[0]);                                                         \
+            pr0[1] = __builtin_amdgcn_exp2f(ar0[1]);                                                         \
+        }                                                                                                    \
+        ar0[0] = __builtin_fmaf(s_cur[0][2 * (x)], c2, -st.mref[0]);                                         \
+        ar0[1] = __builtin_fmaf(s_cur[0][2 * (x) + 1], c2, -st.mref[0]);                                     \
+        asm volatile("" : "+v"(pr0), "+v"(ar0));                                                             \
         __builtin_amdgcn_sched_barrier(0);                                                                   \
     }
     PBS_X_STEP(0) PBS_X_STEP(1) PBS_X_STEP(2) PBS_X_STEP(3) PBS_X_STEP(4) PBS_X_STEP(5) PBS_X_STEP(6) PBS_X_STEP(7)
+    PBS_PACK0(6)
+    pr0[0] = __builtin_amdgcn_exp2f(ar0[0]);
+    pr0[1] = __builtin_amdgcn_exp2f(ar0[1]);
+    PBS_PACK0(7)
+#undef PBS_PACK0
 #undef PBS_X_STEP
     st.l[0] += rsum0;
     st.bad = st.bad || !(rsum0 <= kBigRowSum);
@@ -287,17 +309,36 @@ __device__ __forceinline__ void step(State &st, floatx16 (&s_cur)[2], floatx16 (
     // MFMA i of a group works on fragment PBS_MQ(i): the four O^T tiles with the first 16 keys, then with the other
     // 16, so that consecutive MFMAs never share an accumulator
 #define PBS_MQ(i) ((((i) & 3) << 1) | ((i) >> 2))
+    floatx2 pr1 = {0.0f, 0.0f}, ar1 = {0.0f, 0.0f};
+#define PBS_PACK1(q)                                                                                         \
+    {                                                                                                        \
+        const bf16x2 t2 = __builtin_convertvector(pr1, bf16x2);                                              \
+        const bf16x2 ones = {(bf16_t)1.0f, (bf16_t)1.0f};                                                    \
+        rsum1 = __builtin_amdgcn_fdot2_f32_bf16(t2, ones, rsum1, false);                                     \
+        pf[1][(q) >> 2][2 * ((q) & 3)] = t2[0];                                                              \
+        pf[1][(q) >> 2][2 * ((q) & 3) + 1] = t2[1];                                                          \
+    }
 #define PBS_Y_STEP(q)                                                                                        \
     {                                                                                                        \
         st.acc_o[PBS_MQ(q) >> 1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                               \
             vf[PBS_MQ(q)], pf[0][PBS_MQ(q) & 1], st.acc_o[PBS_MQ(q) >> 1][0], 0, 0, 0);                      \
         kf[q] = *reinterpret_cast<const bf16x8 *>(kl + (q) * 32);                                            \
-        const bf16x2 t2 = exp2_pack2(s_cur[1][2 * (q)], s_cur[1][2 * (q) + 1], c2, st.mref[1], rsum1);       \
-        pf[1][(q) >> 2][2 * ((q) & 3)] = t2[0];                                                              \
-        pf[1][(q) >> 2][2 * ((q) & 3) + 1] = t2[1];                                                          \
+        if ((q) > 1) PBS_PACK1((q) - 2)                                                                      \
+        if ((q) > 0) {                                                                                       \
+            pr1[0] = __builtin_amdgcn_exp2f(ar1[0]);                                                         \
+            pr1[1] = __builtin_amdgcn_exp2f(ar1[1]);                                                         \
+        }                                                                                                    \
+        ar1[0] = __builtin_fmaf(s_cur[1][2 * (q)], c2, -st.mref[1]);                                         \
+        ar1[1] = __builtin_fmaf(s_cur[1][2 * (q) + 1], c2, -st.mref[1]);                                     \
+        asm volatile("" : "+v"(pr1), "+v"(ar1));                                                             \
         __builtin_amdgcn_sched_barrier(0);                                                                   \
     }
     PBS_Y_STEP(0) PBS_Y_STEP(1) PBS_Y_STEP(2) PBS_Y_STEP(3) PBS_Y_STEP(4) PBS_Y_STEP(5) PBS_Y_STEP(6) PBS_Y_STEP(7)
+    PBS_PACK1(6)
+    pr1[0] = __builtin_amdgcn_exp2f(ar1[0]);
+    pr1[1] = __builtin_amdgcn_exp2f(ar1[1]);
+    PBS_PACK1(7)
+#undef PBS_PACK1
 #undef PBS_Y_STEP
     st.l[1] += rsum1;
     st.bad = st.bad || !(rsum1 <= kBigRowSum);
