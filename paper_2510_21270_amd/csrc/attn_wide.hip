@@ -8,14 +8,18 @@
 //     scores of the NEXT sub-tile, the O^T update of the other query tile), so the matrix pipe does not depend on a
 //     second wave happening to be in the opposite phase.
 // Key blocks are consumed in sub-tiles of 32 keys.  Sub-tile u of a list chunk covers keys [32 p, 32 p + 32),
-// p = u % 4, of listed block u / 4 and lives in LDS stage p of a 4-deep ring filled by asynchronous buffer->LDS
-// loads.  Iteration t:
-//     X:  S(t + 1) MFMAs        || softmax(t) of query tile 0 || V'^T fragment reads of sub-tile t
-//     Y:  O^T += ... tile 0     || softmax(t) of query tile 1 || K' fragment reads of sub-tile t + 2
-//     Z:  O^T += ... tile 1     || barrier (every load issued so far has landed; stage t is free), then the
-//                                  loads of sub-tile t + 4 into stage t
+// p = u % 4, of listed block u / 4.  A wave has a single instruction stream to itself, so the loop is a three-deep
+// software pipeline in which no MFMA of an iteration depends on the vector arithmetic of the same iteration, and that
+// arithmetic is spread evenly over the iteration's 32 MFMAs.  Iteration t:
+//     MFMAs  0..15:  S(t + 1) = K'(t + 1) Q'^T, both query tiles          || V'^T fragment reads of sub-tile t - 1
+//     MFMAs 16..31:  O^T += V'^T(t - 1) P^T(t - 1), both query tiles      || K' fragment reads of sub-tile t + 2,
+//                    barrier (every load issued so far has landed; the stage read above is free), then the loads
+//                    of K'(t + 4) and V'^T(t + 3), one per MFMA
+//     all along:     P^T(t) = softmax arithmetic on S(t), one score pair per two MFMAs
+// LDS holds a 4-deep ring of stages filled by asynchronous buffer->LDS loads; stage p holds the K' part p and the
+// V'^T part (p + 3) % 4 of their blocks, which is what iteration t = p (mod 4) frees and refills.
 // A sub-tile that is not plain (token-level mask, queries without a visible key so far) first rewrites its scores
-// and references in a separate block, then goes through the same groups.
+// and references in a separate block, then goes through the same code.
 #include "pbs_host.h"
 
 namespace pbs {
@@ -23,11 +27,8 @@ namespace wide {
 
 constexpr int BLOCK = 128, D = 128;
 constexpr int KS = 32;                                     // keys per sub-tile
-constexpr int kKRowB = 272;                                // K' row in LDS: 256 bytes + 16 of padding
-constexpr int kVRowB = 80;                                 // V'^T row in LDS: 32 keys x 2 bytes + 16 of padding
-constexpr int kKChunks = 9;                                // 32 x 272 = 8704 bytes -> nine 1 KiB load chunks
-constexpr int kVChunks = 10;                               // 128 x 80 = 10240 bytes
-constexpr int kLoadsPerWave = 10;                          // 16-byte-per-lane loads a wave issues per stage
+constexpr int kStageB = 8192;                              // K' sub-tile: 32 rows x 256 B; V'^T sub-tile: 128 rows x 64 B
+constexpr int kLoadsPerWave = 8;                           // 16-byte-per-lane loads a wave issues per stage
 constexpr int kList = 256;                                 // listed blocks staged in LDS at a time
 constexpr int kXcds = 8, kCohort = 64;
 constexpr float kLog2eF = 1.4426950408889634f;
@@ -42,11 +43,14 @@ constexpr float kBigRowSum = 1.8446744e19f;                // 2^64
 typedef __attribute__((address_space(3))) void *lptr_t;
 
 // One ring stage.  Each stage is a separate __shared__ variable so that the compiler can tell a fragment read of
-// one stage from an asynchronous load into another.
+// one stage from an asynchronous load into another.  Rows are not padded; instead the 16-byte pieces of a row are
+// stored XOR-permuted so that the fragment reads below (16 lanes = 16 rows at one logical column) fall into 16
+// different bank groups:
+//   k: row r (256 B) holds key swap23(r) of the sub-tile, its logical piece c (of 16) at place c ^ (r % 16);
+//   v: row e (64 B) holds V'^T[e][32 keys], its logical piece c (of 4) at place c ^ ((e / 4) % 4).
 struct __align__(16) Stage {
-    unsigned char k[kKChunks * 1024];                      // row r holds key swap23(r) of the sub-tile
-    unsigned char v[kVChunks * 1024];                      // row e holds V'^T[e][32 keys]
-    int pos[64];                                           // original positions of the 32 keys (rest unused)
+    unsigned char k[kStageB];
+    unsigned char v[kStageB];
 };
 
 __device__ __forceinline__ int swap23(int m) { return (m & ~12) | ((m & 4) << 1) | ((m & 8) >> 1); }
@@ -55,81 +59,72 @@ struct TileBuffers {
     __amdgpu_buffer_rsrc_t k, v, pos;
 };
 
-// The 19 chunks of a stage are loaded by the same ten instructions in both waves, with per-wave scalar operands:
-// wave 0 takes the nine K' chunks and V'^T chunk 9, wave 1 takes V'^T chunks 0..8 (and chunk 8 once more, so that
-// no branch on the wave index surrounds the instructions).  The 32 key positions ride on eight lanes of wave 0.
-// o[c]: per-lane byte offset, inside one key block / one sub-tile, of what this lane moves in load c.
+// A stage is 16 chunks of 1 KiB, one load instruction each (64 lanes x 16 bytes, consecutive in LDS).  Both waves
+// execute the same eight instructions with per-wave operands: wave 0 brings the K' sub-tile, wave 1 the V'^T one.
+// dma[c]: byte offset inside one key block (K': inside the sub-tile) of the piece this lane moves in load c.
+// kfr[x], vfr[k2]: byte offsets inside a stage's k / v array of this lane's fragment reads.
 struct LaneOffsets {
-    uint32_t o[kLoadsPerWave];
+    uint32_t dma[kLoadsPerWave];
+    uint32_t kfr[8], vfr[2];
 };
 
 __device__ __forceinline__ uint32_t k_lane_offset(int chunk, int lane)
 {
-    const int pos = chunk * 1024 + lane * 16;
-    const int row = pos / kKRowB, col = pos % kKRowB;
-    return row < KS ? (uint32_t)(swap23(row) * 256 + (col < 256 ? col : 0)) : 0u;   // tail of chunk 8: padding
+    const int row = chunk * 4 + (lane >> 4), place = lane & 15;
+    return (uint32_t)(swap23(row) * 256 + ((place ^ (row & 15)) << 4));
 }
 
 __device__ __forceinline__ uint32_t v_lane_offset(int chunk, int lane)
 {
-    const int pos = chunk * 1024 + lane * 16;
-    const int row = pos / kVRowB, col = pos % kVRowB;
-    return (uint32_t)(row * (BLOCK * 2) + (col < KS * 2 ? col : 0));
+    const int row = chunk * 16 + (lane >> 2), place = lane & 3;
+    return (uint32_t)(row * (BLOCK * 2) + ((place ^ ((row >> 2) & 3)) << 4));
 }
 
 __device__ __forceinline__ LaneOffsets lane_offsets(int wave, int lane)
 {
     LaneOffsets r;
+    const int ln = lane & 31, lh = lane >> 5;
 #pragma unroll
-    for (int c = 0; c < kKChunks; ++c) r.o[c] = wave == 0 ? k_lane_offset(c, lane) : v_lane_offset(c, lane);
-    r.o[kKChunks] = v_lane_offset(wave == 0 ? 9 : 8, lane);
+    for (int c = 0; c < kLoadsPerWave; ++c) r.dma[c] = wave == 0 ? k_lane_offset(c, lane) : v_lane_offset(c, lane);
+    // K' fragment x: logical piece 2 x + h of row n;  V'^T fragment (dt, k2): logical piece 2 k2 + h of row 32 dt + n
+#pragma unroll
+    for (int x = 0; x < 8; ++x) r.kfr[x] = (uint32_t)(ln * 256 + (((2 * x + lh) ^ (ln & 15)) << 4));
+#pragma unroll
+    for (int k2 = 0; k2 < 2; ++k2) r.vfr[k2] = (uint32_t)(ln * 64 + (((2 * k2 + lh) ^ ((ln >> 2) & 3)) << 4));
     return r;
 }
 
 // Scalar operands of the loads of part P of block j into stage sg.
 struct StageLoad {
-    __amdgpu_buffer_rsrc_t rsrc;       // loads 0..8
-    int soff, soff_v, soff_pos;        // scalar byte offsets: loads 0..8, load 9 (always V'^T), positions
-    unsigned char *dst, *dst9;         // LDS destinations of load 0 and of load 9
+    __amdgpu_buffer_rsrc_t rsrc;
+    int soff;                          // scalar byte offset of the sub-tile in the tensor
+    unsigned char *dst;                // LDS destination of load 0
 };
 
+// Stage P receives the K' part P of block jk and the V'^T part (P + 3) % 4 of block jv.
 template <int P>
-__device__ __forceinline__ StageLoad stage_load(Stage &sg, const TileBuffers &buf, int j, int wave)
+__device__ __forceinline__ StageLoad stage_load(Stage &sg, const TileBuffers &buf, int jk, int jv, int wave)
 {
     StageLoad a;
-    const int slot0 = j * BLOCK + P * KS;
-    a.soff_v = j * (D * BLOCK * 2) + P * (KS * 2);
-    a.soff_pos = slot0 * 4;
     a.rsrc = wave == 0 ? buf.k : buf.v;
-    a.soff = wave == 0 ? slot0 * 256 : a.soff_v;
+    a.soff = wave == 0 ? (jk * BLOCK + P * KS) * 256 : jv * (D * BLOCK * 2) + ((P + 3) & 3) * (KS * 2);
     a.dst = wave == 0 ? sg.k : sg.v;
-    a.dst9 = sg.v + (wave == 0 ? 9 : 8) * 1024;
     return a;
 }
 
-// load c of the ten
+// load c of the eight
 template <int C>
-__device__ __forceinline__ void issue_load(const StageLoad &a, const TileBuffers &buf, const LaneOffsets &off)
+__device__ __forceinline__ void issue_load(const StageLoad &a, const LaneOffsets &off)
 {
-    if (C < kKChunks) __builtin_amdgcn_raw_ptr_buffer_load_lds(a.rsrc, (lptr_t)(a.dst + C * 1024), 16, off.o[C], a.soff, 0, 0);
-    else __builtin_amdgcn_raw_ptr_buffer_load_lds(buf.v, (lptr_t)a.dst9, 16, off.o[kKChunks], a.soff_v, 0, 0);
-}
-
-// original positions of the sub-tile's 32 keys: 16 bytes on each of the first eight lanes of wave 0
-__device__ __forceinline__ void issue_positions(Stage &sg, const StageLoad &a, const TileBuffers &buf, int wave, int lane)
-{
-    if (wave == 0 && lane < 8) __builtin_amdgcn_raw_ptr_buffer_load_lds(buf.pos, (lptr_t)sg.pos, 16, lane * 16, a.soff_pos, 0, 0);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(a.rsrc, (lptr_t)(a.dst + C * 1024), 16, off.dma[C], a.soff, 0, 0);
 }
 
 template <int P>
-__device__ __forceinline__ void issue_stage(Stage &sg, const TileBuffers &buf, const LaneOffsets &off, int j, int wave,
-                                            int lane)
+__device__ __forceinline__ void issue_stage(Stage &sg, const TileBuffers &buf, const LaneOffsets &off, int j, int wave)
 {
-    const StageLoad a = stage_load<P>(sg, buf, j, wave);
-    issue_load<0>(a, buf, off); issue_load<1>(a, buf, off); issue_load<2>(a, buf, off); issue_load<3>(a, buf, off);
-    issue_load<4>(a, buf, off); issue_load<5>(a, buf, off); issue_load<6>(a, buf, off); issue_load<7>(a, buf, off);
-    issue_load<8>(a, buf, off); issue_load<9>(a, buf, off);
-    issue_positions(sg, a, buf, wave, lane);
+    const StageLoad a = stage_load<P>(sg, buf, j, j, wave);
+    issue_load<0>(a, off); issue_load<1>(a, off); issue_load<2>(a, off); issue_load<3>(a, off);
+    issue_load<4>(a, off); issue_load<5>(a, off); issue_load<6>(a, off); issue_load<7>(a, off);
 }
 
 // Every asynchronous load of this wave has landed, then all waves meet: the stages loaded so far are complete.
@@ -139,6 +134,18 @@ __device__ __forceinline__ void sync_stages()
     __syncthreads();
 }
 
+// The loop's meeting point.  Each wave has waited for all of its loads except the eight it issued in the previous
+// iteration, and for its fragment reads; after the barrier the loads of every wave up to two iterations back are
+// complete.  That is all an iteration needs: it reads K' fragments loaded two iterations earlier and V'^T fragments
+// loaded four iterations earlier, so a load has two full iterations to arrive.  (A plain barrier instruction, not
+// __syncthreads(): the fence of the latter would wait for every load.)
+__device__ __forceinline__ void sync_older_stages()
+{
+    __builtin_amdgcn_s_waitcnt(0x0078);                    // vmcnt(8) lgkmcnt(0), gfx9 encoding
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+}
+
 struct State {
     floatx16 acc_o[4][2];
     float mref[2], l[2];    // reference (log2 units) and sum of exp2(s*c2 - mref), this lane's half of the keys
@@ -146,21 +153,10 @@ struct State {
     bool bad;               // a probability outgrew the fixed reference: this query block is redone by the caller
 };
 
-__device__ __forceinline__ void load_kf(bf16x8 (&kf)[8], const Stage &sg, int ln, int lh)
+__device__ __forceinline__ void load_kf(bf16x8 (&kf)[8], const Stage &sg, const LaneOffsets &off)
 {
-    const unsigned char *kl = sg.k + ln * kKRowB + lh * 16;
 #pragma unroll
-    for (int x = 0; x < 8; ++x) kf[x] = *reinterpret_cast<const bf16x8 *>(kl + x * 32);
-}
-
-__device__ __forceinline__ void load_vf(bf16x8 (&vf)[8], const Stage &sg, int ln, int lh)
-{
-    const unsigned char *vl = sg.v + ln * kVRowB + lh * 16;
-#pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-        for (int k2 = 0; k2 < 2; ++k2)
-            vf[2 * dt + k2] = *reinterpret_cast<const bf16x8 *>(vl + dt * 32 * kVRowB + k2 * 32);
+    for (int x = 0; x < 8; ++x) kf[x] = *reinterpret_cast<const bf16x8 *>(sg.k + off.kfr[x]);
 }
 
 // Score MFMAs are written as assembly statements so that their operands sit where this kernel needs them: the
@@ -215,16 +211,17 @@ __device__ __forceinline__ bf16x2 exp2_pack2(float s0, float s1, float c2, float
 // become -inf, i.e. probability 0), and for queries that meet their first visible key the reference, set to the row
 // maximum of this sub-tile.  A reference, once set, never moves (see the note on kBigRowSum), so O^T is never
 // rescaled and the softmax itself is the same code for every sub-tile.
-__device__ __forceinline__ void prepare_tile(State &st, int nt, floatx16 &s, const int *kpos, int room, bool masked,
-                                             int qpos, float c2, int lh)
+__device__ __forceinline__ void prepare_tile(State &st, int nt, floatx16 &s, __amdgpu_buffer_rsrc_t kpos, int slot0,
+                                             int room, bool masked, int qpos, float c2, int lh)
 {
     if (masked) {
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
             const int k8 = 16 * u + 8 * lh;                    // 8 consecutive keys of this lane
-            const int4 a = *reinterpret_cast<const int4 *>(kpos + k8);
-            const int4 b = *reinterpret_cast<const int4 *>(kpos + k8 + 4);
-            const int kp[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+            // original positions of the keys; a read past the end of the sequence returns 0 and is masked by lim
+            const uintx4 a = __builtin_amdgcn_raw_buffer_load_b128(kpos, k8 * 4, slot0 * 4, 0);
+            const uintx4 b = __builtin_amdgcn_raw_buffer_load_b128(kpos, k8 * 4 + 16, slot0 * 4, 0);
+            const int kp[8] = {(int)a[0], (int)a[1], (int)a[2], (int)a[3], (int)b[0], (int)b[1], (int)b[2], (int)b[3]};
             const int lim = room - k8;                         // keys x >= lim of this group do not exist
 #pragma unroll
             for (int x = 0; x < 8; ++x)
@@ -242,137 +239,167 @@ __device__ __forceinline__ void prepare_tile(State &st, int nt, floatx16 &s, con
     }
 }
 
-// One iteration: sub-tile (block j, part P) is finished -- softmax and O^T update -- while the scores of the next
-// sub-tile are formed.  s_cur: scores of this sub-tile (from the previous iteration); s_nxt: scores of the next one.
-// kf holds the K' fragments of the next sub-tile on entry and those of the one after it on exit.
-// sg_v: this sub-tile's stage (V'^T, positions); once every wave has read it (barrier after group Y) it receives
-// part P of block j_load, four sub-tiles ahead.  sg_k: stage of the sub-tile after the next (K' fragments).
+// One iteration t (t = P mod 4) of the pipeline described at the top of the file.
+// s_cur: scores of sub-tile t (formed by the previous iteration); s_nxt: receives the scores of sub-tile t + 1.
+// kf: K' fragments of sub-tile t + 1 on entry, of sub-tile t + 2 on exit.
+// pf_prev: probabilities of sub-tile t - 1 (from the previous iteration); pf_new: receives those of sub-tile t.
+// sg_v: stage P, whose V'^T part belongs to sub-tile t - 1; after the barrier it receives the K' part P of block jk
+// and the V'^T part (P + 3) % 4 of block jv.  sg_k: stage (P + 2) % 4, K' fragments of sub-tile t + 2.
+// slot0 / room / masked describe sub-tile t.
 template <int P>
 __device__ __forceinline__ void step(State &st, floatx16 (&s_cur)[2], floatx16 (&s_nxt)[2], bf16x8 (&kf)[8],
-                                     const bf16x8 (&qf)[2][8], Stage &sg_v, const Stage &sg_k, const int (&qpos)[2],
-                                     int room, bool masked, float c2, int ln, int lh, const TileBuffers &buf,
-                                     const LaneOffsets &off, int j_load, int wave, int lane)
+                                     const bf16x8 (&qf)[2][8], const bf16x8 (&pf_prev)[2][2], bf16x8 (&pf_new)[2][2],
+                                     Stage &sg_v, const Stage &sg_k, const int (&qpos)[2], int slot0, int room,
+                                     bool masked, float c2, int lh, const TileBuffers &buf, const LaneOffsets &off,
+                                     int jk, int jv, int wave)
 {
-    bf16x8 vf[8], pf[2][2];
+    bf16x8 vf[8];
     if (masked || !__all(st.seen[0] && st.seen[1])) {
         asm volatile("" ::: "memory");                     // keeps this rare block out of the straight-line code
-        prepare_tile(st, 0, s_cur[0], sg_v.pos, room, masked, qpos[0], c2, lh);
-        prepare_tile(st, 1, s_cur[1], sg_v.pos, room, masked, qpos[1], c2, lh);
+        prepare_tile(st, 0, s_cur[0], buf.pos, slot0, room, masked, qpos[0], c2, lh);
+        prepare_tile(st, 1, s_cur[1], buf.pos, slot0, room, masked, qpos[1], c2, lh);
     }
     __builtin_amdgcn_sched_barrier(0);
-    // ---- X (the score MFMAs are opaque statements, so the interleaving with the softmax of tile 0 is written out)
-    const unsigned char *vl = sg_v.v + ln * kVRowB + lh * 16;
-    float rsum0 = 0.0f;
-    // The exponentials of pair x are issued in slot x, their pack and row sum in slot x + 1, so that no instruction
-    // waits on the result of the one just before it.
-    floatx2 pr0 = {0.0f, 0.0f}, ar0 = {0.0f, 0.0f};
-#define PBS_PACK0(x)                                                                                         \
+    // Softmax of score pair q (query tile q / 8, scores 2 (q % 8) and + 1) in three stages, issued in consecutive
+    // MFMA slots so that no instruction waits on the one just before it: multiply-add in slot 2 q, exponentials in
+    // slot 2 q + 1, rounding / row sum / pack in slot 2 q + 2.
+    float rsum[2] = {0.0f, 0.0f};
+    floatx2 pr = {0.0f, 0.0f}, ar = {0.0f, 0.0f};
+#ifdef PBS_PIN_DOT2
+#define PBS_PIN_RSUM(r) asm volatile("" : "+v"(r));
+#else
+#define PBS_PIN_RSUM(r)
+#endif
+#define PBS_SM_FMA(q)                                                                                        \
     {                                                                                                        \
-        const bf16x2 t2 = __builtin_convertvector(pr0, bf16x2);                                              \
-        const bf16x2 ones = {(bf16_t)1.0f, (bf16_t)1.0f};                                                    \
-        rsum0 = __builtin_amdgcn_fdot2_f32_bf16(t2, ones, rsum0, false);                                     \
-        pf[0][(x) >> 2][2 * ((x) & 3)] = t2[0];                                                              \
-        pf[0][(x) >> 2][2 * ((x) & 3) + 1] = t2[1];                                                          \
+        ar[0] = __builtin_fmaf(s_cur[(q) >> 3][2 * ((q) & 7)], c2, -st.mref[(q) >> 3]);                      \
+        ar[1] = __builtin_fmaf(s_cur[(q) >> 3][2 * ((q) & 7) + 1], c2, -st.mref[(q) >> 3]);                  \
     }
-#define PBS_X_STEP(x)                                                                                        \
+#define PBS_SM_EXP(q)                                                                                        \
     {                                                                                                        \
-        if ((x) == 0) {                                                                                      \
-            s_mfma_first<0>(s_nxt[0], kf[0], qf[0][0]);                                                      \
-            s_mfma_first<1>(s_nxt[1], kf[0], qf[1][0]);                                                      \
+        pr[0] = __builtin_amdgcn_exp2f(ar[0]);                                                               \
+        pr[1] = __builtin_amdgcn_exp2f(ar[1]);                                                               \
+    }
+#define PBS_SM_PACK(q)                                                                                       \
+    {                                                                                                        \
+        bf16x2 t2 = __builtin_convertvector(pr, bf16x2);                                                     \
+        asm volatile("" : "+v"(t2));                       /* the pack happens here, not where it is consumed */ \
+        const bf16x2 ones = {(bf16_t)1.0f, (bf16_t)1.0f};                                                    \
+        rsum[(q) >> 3] = __builtin_amdgcn_fdot2_f32_bf16(t2, ones, rsum[(q) >> 3], false);                   \
+        PBS_PIN_RSUM(rsum[(q) >> 3])                                                                         \
+        pf_new[(q) >> 3][((q) & 7) >> 2][2 * ((q) & 3)] = t2[0];                                             \
+        pf_new[(q) >> 3][((q) & 7) >> 2][2 * ((q) & 3) + 1] = t2[1];                                         \
+    }
+    // vector work of MFMA slot m
+#define PBS_SM_SLOT(m)                                                                                       \
+    {                                                                                                        \
+        if (((m) & 1) == 0) {                                                                                \
+            if ((m) > 0) PBS_SM_PACK((((m) >> 1) + 15) & 15)                                                 \
+            PBS_SM_FMA((m) >> 1)                                                                             \
         } else {                                                                                             \
-            s_mfma_next<0>(s_nxt[0], kf[x], qf[0][x]);                                                       \
-            s_mfma_next<1>(s_nxt[1], kf[x], qf[1][x]);                                                       \
+            PBS_SM_EXP((m) >> 1)                                                                             \
         }                                                                                                    \
-        vf[x] = *reinterpret_cast<const bf16x8 *>(vl + ((x) >> 1) * 32 * kVRowB + ((x) & 1) * 32);           \
-        if ((x) > 1) PBS_PACK0((x) - 2)                                                                      \
-        if ((x) > 0) {                                                                                       \
-            pr0[0] = __builtin_amdgcn_exp2f(ar0[0]);                                                         \
-            pr0[1] = __builtin_amdgcn_exp2f(ar0[1]);                                                         \
-        }                                                                                                    \
-        ar0[0] = __builtin_fmaf(s_cur[0][2 * (x)], c2, -st.mref[0]);                                         \
-        ar0[1] = __builtin_fmaf(s_cur[0][2 * (x) + 1], c2, -st.mref[0]);                                     \
-        asm volatile("" : "+v"(pr0), "+v"(ar0));                                                             \
+        asm volatile("" : "+v"(pr), "+v"(ar));                                                               \
         __builtin_amdgcn_sched_barrier(0);                                                                   \
     }
-    PBS_X_STEP(0) PBS_X_STEP(1) PBS_X_STEP(2) PBS_X_STEP(3) PBS_X_STEP(4) PBS_X_STEP(5) PBS_X_STEP(6) PBS_X_STEP(7)
-    PBS_PACK0(6)
-    pr0[0] = __builtin_amdgcn_exp2f(ar0[0]);
-    pr0[1] = __builtin_amdgcn_exp2f(ar0[1]);
-    PBS_PACK0(7)
-#undef PBS_PACK0
-#undef PBS_X_STEP
-    st.l[0] += rsum0;
-    st.bad = st.bad || !(rsum0 <= kBigRowSum);
-    // ---- Y: O^T update of tile 0 || softmax of tile 1 || K' fragments of the sub-tile after the next
-    float rsum1 = 0.0f;
-    const unsigned char *kl = sg_k.k + ln * kKRowB + lh * 16;
-    // MFMA i of a group works on fragment PBS_MQ(i): the four O^T tiles with the first 16 keys, then with the other
-    // 16, so that consecutive MFMAs never share an accumulator
+    // ---- slots 0..15: score MFMAs of sub-tile t + 1 (opaque statements, so the interleaving is written out).
+    // The V'^T fragments are read in slots 0..7.  After slot 11 the waves meet: every wave has those fragments in
+    // registers (stage sg_v is free) and every load issued so far has landed; the refill of sg_v is issued under
+    // slots 12..19.  K' fragment reads of sub-tile t + 2 take slots 16..23.
+#define PBS_S_MFMA(m)                                                                                        \
+    {                                                                                                        \
+        if ((m) == 0) s_mfma_first<0>(s_nxt[0], kf[0], qf[0][0]);                                            \
+        else if ((m) == 1) s_mfma_first<1>(s_nxt[1], kf[0], qf[1][0]);                                       \
+        else if (((m) & 1) == 0) s_mfma_next<0>(s_nxt[0], kf[(m) >> 1], qf[0][(m) >> 1]);                    \
+        else s_mfma_next<1>(s_nxt[1], kf[(m) >> 1], qf[1][(m) >> 1]);                                        \
+        asm volatile("" : "+v"(pr), "+v"(ar));             /* the slot's vector work follows its MFMA */     \
+    }
+#define PBS_VF_SLOT(m)                                                                                       \
+    {                                                                                                        \
+        PBS_S_MFMA(m)                                                                                        \
+        vf[m] = *reinterpret_cast<const bf16x8 *>(sg_v.v + off.vfr[(m) & 1] + ((m) >> 1) * 2048);            \
+        PBS_SM_SLOT(m)                                                                                       \
+    }
+#define PBS_S_SLOT(m)                                                                                        \
+    {                                                                                                        \
+        PBS_S_MFMA(m)                                                                                        \
+        PBS_SM_SLOT(m)                                                                                       \
+    }
+#define PBS_SLD_SLOT(m)                                                                                      \
+    {                                                                                                        \
+        PBS_S_MFMA(m)                                                                                        \
+        issue_load<(m) - 12>(ld, off);                                                                       \
+        PBS_SM_SLOT(m)                                                                                       \
+    }
+    PBS_VF_SLOT(0) PBS_VF_SLOT(1) PBS_VF_SLOT(2) PBS_VF_SLOT(3) PBS_VF_SLOT(4) PBS_VF_SLOT(5) PBS_VF_SLOT(6) PBS_VF_SLOT(7)
+    PBS_S_SLOT(8) PBS_S_SLOT(9) PBS_S_SLOT(10) PBS_S_SLOT(11)
+    sync_older_stages();
+    const StageLoad ld = stage_load<P>(sg_v, buf, jk, jv, wave);
+    PBS_SLD_SLOT(12) PBS_SLD_SLOT(13) PBS_SLD_SLOT(14) PBS_SLD_SLOT(15)
+#undef PBS_SLD_SLOT
+#undef PBS_S_SLOT
+#undef PBS_VF_SLOT
+#undef PBS_S_MFMA
+    // ---- slots 16..31: O^T update with sub-tile t - 1.  MFMA i of a query tile works on fragment PBS_MQ(i): the four
+    // O^T tiles with the first 16 keys, then with the other 16, so that consecutive MFMAs never share an accumulator.
 #define PBS_MQ(i) ((((i) & 3) << 1) | ((i) >> 2))
-    floatx2 pr1 = {0.0f, 0.0f}, ar1 = {0.0f, 0.0f};
-#define PBS_PACK1(q)                                                                                         \
+#define PBS_PV_MFMA(n)                                                                                       \
+    st.acc_o[PBS_MQ((n) & 7) >> 1][(n) >> 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                      \
+        vf[PBS_MQ((n) & 7)], pf_prev[(n) >> 3][PBS_MQ((n) & 7) & 1], st.acc_o[PBS_MQ((n) & 7) >> 1][(n) >> 3], 0, 0, 0);
+#define PBS_KF_READ(n) kf[n] = *reinterpret_cast<const bf16x8 *>(sg_k.k + off.kfr[n]);
+#define PBS_PLD_SLOT(n)                                                                                      \
     {                                                                                                        \
-        const bf16x2 t2 = __builtin_convertvector(pr1, bf16x2);                                              \
-        const bf16x2 ones = {(bf16_t)1.0f, (bf16_t)1.0f};                                                    \
-        rsum1 = __builtin_amdgcn_fdot2_f32_bf16(t2, ones, rsum1, false);                                     \
-        pf[1][(q) >> 2][2 * ((q) & 3)] = t2[0];                                                              \
-        pf[1][(q) >> 2][2 * ((q) & 3) + 1] = t2[1];                                                          \
+        PBS_PV_MFMA(n)                                                                                       \
+        issue_load<(n) + 4>(ld, off);                                                                        \
+        PBS_KF_READ(n)                                                                                       \
+        PBS_SM_SLOT(16 + (n))                                                                                \
     }
-#define PBS_Y_STEP(q)                                                                                        \
+#define PBS_KF_SLOT(n)                                                                                       \
     {                                                                                                        \
-        st.acc_o[PBS_MQ(q) >> 1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                               \
-            vf[PBS_MQ(q)], pf[0][PBS_MQ(q) & 1], st.acc_o[PBS_MQ(q) >> 1][0], 0, 0, 0);                      \
-        kf[q] = *reinterpret_cast<const bf16x8 *>(kl + (q) * 32);                                            \
-        if ((q) > 1) PBS_PACK1((q) - 2)                                                                      \
-        if ((q) > 0) {                                                                                       \
-            pr1[0] = __builtin_amdgcn_exp2f(ar1[0]);                                                         \
-            pr1[1] = __builtin_amdgcn_exp2f(ar1[1]);                                                         \
-        }                                                                                                    \
-        ar1[0] = __builtin_fmaf(s_cur[1][2 * (q)], c2, -st.mref[1]);                                         \
-        ar1[1] = __builtin_fmaf(s_cur[1][2 * (q) + 1], c2, -st.mref[1]);                                     \
-        asm volatile("" : "+v"(pr1), "+v"(ar1));                                                             \
-        __builtin_amdgcn_sched_barrier(0);                                                                   \
+        PBS_PV_MFMA(n)                                                                                       \
+        PBS_KF_READ(n)                                                                                       \
+        PBS_SM_SLOT(16 + (n))                                                                                \
     }
-    PBS_Y_STEP(0) PBS_Y_STEP(1) PBS_Y_STEP(2) PBS_Y_STEP(3) PBS_Y_STEP(4) PBS_Y_STEP(5) PBS_Y_STEP(6) PBS_Y_STEP(7)
-    PBS_PACK1(6)
-    pr1[0] = __builtin_amdgcn_exp2f(ar1[0]);
-    pr1[1] = __builtin_amdgcn_exp2f(ar1[1]);
-    PBS_PACK1(7)
-#undef PBS_PACK1
-#undef PBS_Y_STEP
-    st.l[1] += rsum1;
-    st.bad = st.bad || !(rsum1 <= kBigRowSum);
-    // ---- Z: O^T update of tile 1.  Two MFMAs are queued before the barrier, so the matrix pipe has work while the
-    // waves meet; after the barrier every wave is done reading stage sg_v, which is refilled under the rest.
-#define PBS_Z_MFMA(i)                                                                                        \
-    st.acc_o[PBS_MQ(i) >> 1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                                   \
-        vf[PBS_MQ(i)], pf[1][PBS_MQ(i) & 1], st.acc_o[PBS_MQ(i) >> 1][1], 0, 0, 0);
-    PBS_Z_MFMA(0) PBS_Z_MFMA(1)
-    __builtin_amdgcn_sched_barrier(0);
-    sync_stages();
-    const StageLoad ld = stage_load<P>(sg_v, buf, j_load, wave);
-    issue_load<0>(ld, buf, off); issue_load<1>(ld, buf, off);
-    __builtin_amdgcn_sched_barrier(0);
-    PBS_Z_MFMA(2)
-    issue_load<2>(ld, buf, off); issue_load<3>(ld, buf, off);
-    __builtin_amdgcn_sched_barrier(0);
-    PBS_Z_MFMA(3)
-    issue_load<4>(ld, buf, off); issue_load<5>(ld, buf, off);
-    __builtin_amdgcn_sched_barrier(0);
-    PBS_Z_MFMA(4)
-    issue_load<6>(ld, buf, off); issue_load<7>(ld, buf, off);
-    __builtin_amdgcn_sched_barrier(0);
-    PBS_Z_MFMA(5)
-    issue_load<8>(ld, buf, off); issue_load<9>(ld, buf, off);
-    __builtin_amdgcn_sched_barrier(0);
-    PBS_Z_MFMA(6)
-    issue_positions(sg_v, ld, buf, wave, lane);
-    __builtin_amdgcn_sched_barrier(0);
-    PBS_Z_MFMA(7)
-#undef PBS_Z_MFMA
-#undef PBS_MQ
+#define PBS_PV_SLOT(n)                                                                                       \
+    {                                                                                                        \
+        PBS_PV_MFMA(n)                                                                                       \
+        PBS_SM_SLOT(16 + (n))                                                                                \
+    }
+    PBS_PLD_SLOT(0) PBS_PLD_SLOT(1) PBS_PLD_SLOT(2) PBS_PLD_SLOT(3)
+    PBS_KF_SLOT(4) PBS_KF_SLOT(5) PBS_KF_SLOT(6) PBS_KF_SLOT(7)
+    PBS_PV_SLOT(8) PBS_PV_SLOT(9) PBS_PV_SLOT(10) PBS_PV_SLOT(11) PBS_PV_SLOT(12) PBS_PV_SLOT(13) PBS_PV_SLOT(14)
+    PBS_PV_SLOT(15)
+    PBS_SM_PACK(15)
+#undef PBS_PV_SLOT
+#undef PBS_KF_SLOT
+#undef PBS_PLD_SLOT
+#undef PBS_KF_READ
+#undef PBS_PV_MFMA
+#undef PBS_SM_SLOT
+#undef PBS_SM_PACK
+#undef PBS_SM_EXP
+#undef PBS_SM_FMA
+#undef PBS_PIN_RSUM
+    st.l[0] += rsum[0];
+    st.l[1] += rsum[1];
+    st.bad = st.bad || !(rsum[0] <= kBigRowSum) || !(rsum[1] <= kBigRowSum);
     __builtin_amdgcn_sched_barrier(0);
 }
+
+// End of a list chunk: the O^T update with its last sub-tile (part 3 of the last block, in stage 0).
+__device__ __forceinline__ void drain(State &st, const bf16x8 (&pf)[2][2], const Stage &sg, const LaneOffsets &off)
+{
+    bf16x8 vf[8];
+#pragma unroll
+    for (int x = 0; x < 8; ++x) vf[x] = *reinterpret_cast<const bf16x8 *>(sg.v + off.vfr[x & 1] + (x >> 1) * 2048);
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            st.acc_o[PBS_MQ(i) >> 1][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                vf[PBS_MQ(i)], pf[nt][PBS_MQ(i) & 1], st.acc_o[PBS_MQ(i) >> 1][nt], 0, 0, 0);
+}
+#undef PBS_MQ
 
 __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1, 1))) void attn_wide_kernel(
     const bf16_t *__restrict__ Qp, const bf16_t *__restrict__ Kp, const bf16_t *__restrict__ Vt,
@@ -380,7 +407,7 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     const int32_t *__restrict__ col_idx, bf16_t *__restrict__ Op, float *__restrict__ lse,
     int32_t *__restrict__ redo, Geo g)
 {
-    __shared__ Stage sg0, sg1, sg2, sg3;                   // 4 x 19.25 KiB
+    __shared__ Stage sg0, sg1, sg2, sg3;                   // 4 x 16 KiB
     __shared__ int jl[kList];                              // listed blocks of the current chunk, -1 = not admissible
     __shared__ int bad_any;
 
@@ -455,17 +482,22 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         // prologue: the four parts of the first block, its first scores, the K' fragments of part 1
         int jraw = entry(0);
         int jc = jraw < 0 ? 0 : jraw;
-        issue_stage<0>(sg0, buf, off, jc, wave, lane);
-        issue_stage<1>(sg1, buf, off, jc, wave, lane);
-        issue_stage<2>(sg2, buf, off, jc, wave, lane);
-        issue_stage<3>(sg3, buf, off, jc, wave, lane);
+        issue_stage<0>(sg0, buf, off, jc, wave);
+        issue_stage<1>(sg1, buf, off, jc, wave);
+        issue_stage<2>(sg2, buf, off, jc, wave);
+        issue_stage<3>(sg3, buf, off, jc, wave);
         sync_stages();
         floatx16 sa[2], sb[2];
         bf16x8 kf[8];
-        load_kf(kf, sg0, ln, lh);
+        load_kf(kf, sg0, off);
         s_mfma(sa, kf, qf);
         mfma_fence();
-        load_kf(kf, sg1, ln, lh);
+        load_kf(kf, sg1, off);
+        bf16x8 pa[2][2], pb[2][2];                         // probabilities of the previous / the current sub-tile
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int x = 0; x < 8; ++x) pa[u >> 1][u & 1][x] = (bf16_t)0.0f;
         __builtin_amdgcn_sched_barrier(0);
 
         for (int e = 0; e < len; ++e) {
@@ -474,15 +506,19 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
             const int jn = jnraw < 0 ? 0 : jnraw;
             const bool masked = jraw < 0 || jraw >= jmask;
             const int room0 = jraw < 0 ? 0 : g.n - jraw * BLOCK;   // keys of the block that exist
-            // part p: softmax and O^T update of part p; scores of part p + 1; K' fragments of part p + 2 (parts past
-            // 3 are those of the next block); part p of the next block is loaded into the stage part p leaves
-            step<0>(st, sa, sb, kf, qf, sg0, sg2, qpos, room0, masked, c2, ln, lh, buf, off, jn, wave, lane);
-            step<1>(st, sb, sa, kf, qf, sg1, sg3, qpos, room0 - KS, masked, c2, ln, lh, buf, off, jn, wave, lane);
-            step<2>(st, sa, sb, kf, qf, sg2, sg0, qpos, room0 - 2 * KS, masked, c2, ln, lh, buf, off, jn, wave, lane);
-            step<3>(st, sb, sa, kf, qf, sg3, sg1, qpos, room0 - 3 * KS, masked, c2, ln, lh, buf, off, jn, wave, lane);
+            const int slot0 = jc * BLOCK;                          // first key slot of the block
+            // part p: probabilities of part p; scores of part p + 1; O^T update with part p - 1; K' fragments of
+            // part p + 2 (parts outside 0..3 are those of the neighbouring listed blocks).  Stage p is refilled with
+            // K' part p of the next block and V'^T part p - 1 of the next block (part 3 of this block when p = 0).
+            // The first iteration of a chunk updates O^T with zero probabilities.
+            step<0>(st, sa, sb, kf, qf, pa, pb, sg0, sg2, qpos, slot0, room0, masked, c2, lh, buf, off, jn, jc, wave);
+            step<1>(st, sb, sa, kf, qf, pb, pa, sg1, sg3, qpos, slot0 + KS, room0 - KS, masked, c2, lh, buf, off, jn, jn, wave);
+            step<2>(st, sa, sb, kf, qf, pa, pb, sg2, sg0, qpos, slot0 + 2 * KS, room0 - 2 * KS, masked, c2, lh, buf, off, jn, jn, wave);
+            step<3>(st, sb, sa, kf, qf, pb, pa, sg3, sg1, qpos, slot0 + 3 * KS, room0 - 3 * KS, masked, c2, lh, buf, off, jn, jn, wave);
             jraw = jnraw;
             jc = jn;
         }
+        drain(st, pa, sg0, off);
         __builtin_amdgcn_s_waitcnt(0x0F70);                // the loads issued past the end have landed too
     }
 
