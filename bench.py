@@ -215,6 +215,9 @@ def main():
         extras["plain_copy"] = {"ms": ms_copy, "GBps": nbytes / ms_copy / 1e6, "bytes": nbytes}
         extras["unpermute_random_sigma"] = {"ms": ms_sigma, "GBps": (nbytes + sigma.numel() * 4) / ms_sigma / 1e6}
         del scratch, sigma
+        # what the matrix units sustain on their own, with operand bits that cost no / realistic switching power
+        extras["mfma_alone_tflops"] = {"zero_operands": pbs.mfma_rate_probe(False),
+                                       "random_operands": pbs.mfma_rate_probe(True)}
 
     cnt = (row_cnt if given else pipe.row_cnt).cpu().numpy().astype(np.int64)
     visited = int(cnt.sum())
@@ -248,6 +251,8 @@ def main():
         "context": {"paper_h100_128k_ms": {"flashattention": 443.29, "pbs_total": 159.87, "speedup": 2.77},
                     "input_generation_s": t_gen, **extras},
     }
+    if "mfma_alone_tflops" in extras:
+        out["roofline"]["frac_of_mfma_alone_random_operands"] = attn_tflops / extras["mfma_alone_tflops"]["random_operands"]
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(out))

@@ -31,10 +31,11 @@
  *     permuted tensor holds original token idx[p], and idx maps every segment
  *     onto itself.
  *   - K' ("Kp") keeps the [batch, h_kv, n, d] layout.  V' is kept as "Vt":
- *     [batch, h_kv, T, d, block], i.e. every key block stored transposed, the
- *     slots past n in the last block zero-filled.  Vt is produced by
- *     pbs_segment_permute and consumed by pbs_attn_fwd; pbs_vt_bytes gives its
- *     size.
+ *     [batch, h_kv, T, block / G, d, G] with G = min(block, 32), i.e. every
+ *     key block stored as groups of G consecutive key slots, each group
+ *     transposed (feature-major), the slots past n in the last block
+ *     zero-filled.  Vt is produced by pbs_segment_permute and consumed by
+ *     pbs_attn_fwd; pbs_vt_bytes gives its size.
  *   - Supported: dtype PBS_BF16 or PBS_F32; d in {64, 128}; block in
  *     {16, 32, 64, 128}; segment <= 4096; T <= 4096; any n >= 1.  The matrix-core
  *     attention kernel serves PBS_BF16 with d = 128 and block in {64, 128};
@@ -171,6 +172,18 @@ pbs_status pbs_attn_fwd(const pbs_problem *p, const void *Qp, const void *Kp, co
  * partially overlap Op.
  */
 pbs_status pbs_unpermute(const pbs_problem *p, const void *Op, const int32_t *qidx, void *O, void *stream);
+
+/*
+ * Measurement aid, not a step of Algorithm 1: launches a kernel that does nothing but bf16 matrix instructions
+ * (one wave per SIMD on 256 compute units, operands in registers) for `iters` rounds of 32 instructions, with all-zero
+ * operands (random_operands = 0) or pseudo-random ones.  The caller times the launch on `stream`; *flop (host memory)
+ * receives the number of floating-point operations it performs.  The clock of the chip under matrix load depends on
+ * the operand bits, so the rate with random operands is the matrix rate a kernel working on real data can approach.
+ *   sink: device memory, sink_floats >= 65536 float32, overwritten.  iters in [1, 2^22].
+ * Errors: PBS_ERR_NULL, PBS_ERR_SHAPE (iters or sink_floats out of range), PBS_ERR_HIP.
+ */
+pbs_status pbs_mfma_rate_probe(int random_operands, int iters, float *sink, size_t sink_floats, double *flop,
+                               void *stream);
 
 #ifdef __cplusplus
 }

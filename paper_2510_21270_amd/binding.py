@@ -18,7 +18,8 @@ STAGE_KEY_SCORES, STAGE_SEGMENT_PERMUTE, STAGE_BLOCK_MASK, STAGE_ATTN_FWD, STAGE
 FLAG_FORCE_FIRST_BLOCK = 1
 
 EXPORTS = ["pbs_status_string", "pbs_validate", "pbs_workspace_bytes", "pbs_vt_bytes", "pbs_key_scores",
-           "pbs_segment_permute", "pbs_permute_rows", "pbs_block_mask", "pbs_attn_fwd", "pbs_unpermute"]
+           "pbs_segment_permute", "pbs_permute_rows", "pbs_block_mask", "pbs_attn_fwd", "pbs_unpermute",
+           "pbs_mfma_rate_probe"]
 
 
 class PbsError(RuntimeError):
@@ -54,6 +55,7 @@ def load_library():
         lib.pbs_block_mask.argtypes = [P, V, V, V, V, V, V, Z, V]
         lib.pbs_attn_fwd.argtypes = [P, V, V, V, V, V, V, V, V, V, V, Z, V]
         lib.pbs_unpermute.argtypes = [P, V, V, V, V]
+        lib.pbs_mfma_rate_probe.argtypes = [ctypes.c_int, ctypes.c_int, V, Z, ctypes.POINTER(ctypes.c_double), V]
         _lib = lib
     return _lib
 
@@ -102,7 +104,8 @@ def alloc_workspace(p, stage, device="cuda"):
 
 
 def alloc_vt(p, device="cuda"):
-    return torch.empty((p.batch, p.h_kv, T_of(p), p.d, p.block), dtype=torch_dtype(p), device=device)
+    G = min(p.block, 32)                                   # keys per transposed group
+    return torch.empty((p.batch, p.h_kv, T_of(p), p.block // G, p.d, G), dtype=torch_dtype(p), device=device)
 
 
 def _ws_args(p, stage, ws):
@@ -174,6 +177,22 @@ def unpermute(p, Op, qidx, O=None):
         O = Op if qidx is None else torch.empty_like(Op)
     _check(load_library().pbs_unpermute(ctypes.byref(p), _ptr(Op), _ptr(qidx), _ptr(O), _stream()), "pbs_unpermute")
     return O
+
+
+def mfma_rate_probe(random_operands, iters=20000, reps=3):
+    """TFLOP/s of the matrix units alone (best of `reps` launches timed with events on the current stream)."""
+    sink = torch.empty(65536, dtype=torch.float32, device="cuda")
+    flop = ctypes.c_double(0.0)
+    best = 0.0
+    for _ in range(reps + 1):                              # the first launch warms up
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        _check(load_library().pbs_mfma_rate_probe(int(bool(random_operands)), iters, _ptr(sink), sink.numel(),
+                                                  ctypes.byref(flop), _stream()), "pbs_mfma_rate_probe")
+        e1.record()
+        e1.synchronize()
+        best = max(best, flop.value / (e0.elapsed_time(e1) * 1e-3) / 1e12)
+    return best
 
 
 class Pipeline:

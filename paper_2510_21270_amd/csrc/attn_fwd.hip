@@ -100,7 +100,8 @@ __device__ inline LaneOffsets<WAVES> lane_offsets(int wave, int lane)
     for (int y = 0; y < (kVLoads + WAVES - 1) / WAVES; ++y) {
         const int pos = (wave + WAVES * y) * 1024 + lane * 16;
         const int r = pos / kVRowB, col = pos % kVRowB;
-        o.v[y] = (uint32_t)(r * (BLOCK * 2) + (col < 128 ? col : 0));
+        // Vt: groups of 32 keys, each [128 features][32 keys]; the 64 keys of a sub-tile are two groups
+        o.v[y] = (uint32_t)(col < 128 ? ((col >> 6) * 128 + r) * 64 + (col & 63) : r * 64);
     }
     return o;
 }
@@ -120,7 +121,7 @@ __device__ inline void issue_subtile(unsigned char *kbuf, unsigned char *vbuf, i
     for (int y = 0; y < (kVLoads + WAVES - 1) / WAVES; ++y)
         if (y < kVLoads / WAVES || wave < kVLoads % WAVES)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(buf.v, (lptr_t)(vbuf + (wave + WAVES * y) * 1024), 16, off.v[y],
-                                                     j * (128 * BLOCK * 2) + half * (KT * 2), 0, 0);
+                                                     j * (128 * BLOCK * 2) + half * (128 * KT * 2), 0, 0);
     if (masked && wave == WAVES - 1)                       // original positions of the sub-tile's 64 keys
         __builtin_amdgcn_raw_ptr_buffer_load_lds(buf.pos, (lptr_t)kpos, 4, lane * 4, slot0 * 4, 0, 0);
 }
@@ -452,7 +453,7 @@ __global__ __launch_bounds__(256) void attn_vector_kernel(
     constexpr int HALF = D / 2;
     extern __shared__ __align__(16) unsigned char smem_raw[];
     float *kt = reinterpret_cast<float *>(smem_raw);             // [block][D]
-    float *vt = kt + g.block * D;                                // [D][block]
+    float *vt = kt + g.block * D;                                // the block's Vt image: [block / G][D][G]
     int *kpos = reinterpret_cast<int *>(vt + D * g.block);       // [block]
 
     const int i = g.T - 1 - (int)blockIdx.x;
@@ -477,6 +478,7 @@ __global__ __launch_bounds__(256) void attn_vector_kernel(
     const E *Kh = Kp + bhk * (size_t)g.n * D;
     const E *Vh = Vt + bhk * (size_t)g.T * D * g.block;
     const int32_t *kih = kidx + bhk * (size_t)g.n;
+    const int G = vt_group(g.block);
 
     for (int t = 0; t < cnt; ++t) {
         const int j = cols[t];
@@ -509,9 +511,9 @@ __global__ __launch_bounds__(256) void attn_vector_kernel(
             }
             const float p = __expf(s - m);
             l += p;
-            const float *vr = vt + (half * HALF) * g.block + c;
+            const float *vr = vt + ((c / G) * D + half * HALF) * G + c % G;
 #pragma unroll
-            for (int e = 0; e < HALF; ++e) o[e] += p * vr[e * g.block];
+            for (int e = 0; e < HALF; ++e) o[e] += p * vr[e * G];
         }
     }
     if (live) {

@@ -74,10 +74,11 @@ __device__ __forceinline__ uint32_t k_lane_offset(int chunk, int lane)
     return (uint32_t)(swap23(row) * 256 + ((place ^ (row & 15)) << 4));
 }
 
+// Vt keeps a block as four groups of 32 keys, each [128 features][32 keys]: a sub-tile is 8 KiB of consecutive bytes
 __device__ __forceinline__ uint32_t v_lane_offset(int chunk, int lane)
 {
     const int row = chunk * 16 + (lane >> 2), place = lane & 3;
-    return (uint32_t)(row * (BLOCK * 2) + ((place ^ ((row >> 2) & 3)) << 4));
+    return (uint32_t)(row * (KS * 2) + ((place ^ ((row >> 2) & 3)) << 4));
 }
 
 __device__ __forceinline__ LaneOffsets lane_offsets(int wave, int lane)
@@ -107,7 +108,7 @@ __device__ __forceinline__ StageLoad stage_load(Stage &sg, const TileBuffers &bu
 {
     StageLoad a;
     a.rsrc = wave == 0 ? buf.k : buf.v;
-    a.soff = wave == 0 ? (jk * BLOCK + P * KS) * 256 : jv * (D * BLOCK * 2) + ((P + 3) & 3) * (KS * 2);
+    a.soff = wave == 0 ? (jk * BLOCK + P * KS) * 256 : jv * (D * BLOCK * 2) + ((P + 3) & 3) * (D * KS * 2);
     a.dst = wave == 0 ? sg.k : sg.v;
     return a;
 }

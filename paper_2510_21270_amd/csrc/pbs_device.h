@@ -50,6 +50,10 @@ __host__ __device__ inline int first_masked_col(int i, const Geo &g)
     return s < g.G ? s * g.R : i;
 }
 
+// Vt stores every key block as groups of vt_group(block) consecutive key slots, each group transposed:
+// element (group gi, feature e, key k of the group) of a block sits at ((gi * d + e) * vt_group + k).
+__host__ __device__ inline int vt_group(int block) { return block < 32 ? block : 32; }
+
 template <typename T> struct ElemTraits;
 template <> struct ElemTraits<float> {
     __device__ static inline float to_float(float v) { return v; }

@@ -93,9 +93,10 @@ __global__ __launch_bounds__(256) void move_rows_kernel(const uintx4 *__restrict
 // ---------------------------------------------------------------------------------------------
 // V' in the block-transposed layout Vt[bh][j][e][c] = V[bh][kidx[j*block + c]][e] (zero for slots >= n).
 // One workgroup per (key block j, bh): gathered rows go to LDS with coalesced 16-byte reads, the tile is
-// read back column-wise in 4-byte words and leaves as 16-byte pieces of Vt rows, neighbouring lanes writing
-// neighbouring pieces.  LDS row r starts at word r * (row words) + 4 * (r / VEC): the 16-byte skew per group
-// of VEC rows spreads the column-wise reads of one wave over all banks.
+// read back column-wise in 4-byte words and leaves as 16-byte pieces of Vt rows (VEC keys of one feature),
+// neighbouring lanes writing neighbouring pieces of a key group, then the next feature.  LDS row r starts at word
+// r * (row words) + (r / VEC) * (64 / gpp) with gpp pieces per Vt row: the lanes of a wave read gpp pieces x
+// 64 / gpp word columns, which then fall into 64 different banks.
 // E = storage type (2 or 4 bytes); VEC = elements per 16-byte chunk.
 // ---------------------------------------------------------------------------------------------
 template <typename E>
@@ -109,6 +110,9 @@ __global__ __launch_bounds__(256) void gather_vt_kernel(const E *__restrict__ V,
     const int j = blockIdx.x;
     const size_t bh = blockIdx.y;
     const int cpr = d / VEC;
+    const int G = vt_group(block);                         // keys per transposed group
+    const int gpp = G / VEC;                               // 16-byte pieces per Vt row
+    const int skew = 64 / gpp;                             // words; gpp is 2, 4 or 8
     typedef E vec_t __attribute__((ext_vector_type(VEC)));
     for (int c = threadIdx.x; c < block * cpr; c += blockDim.x) {
         const int row = c / cpr, cc = c % cpr;
@@ -118,21 +122,22 @@ __global__ __launch_bounds__(256) void gather_vt_kernel(const E *__restrict__ V,
             const int32_t src = kidx ? kidx[bh * n + slot] : slot;
             if (src >= 0 && src < n) v = *reinterpret_cast<const vec_t *>(V + (bh * n + src) * (size_t)d + cc * VEC);
         }
-        *reinterpret_cast<vec_t *>(tile + row * roww + 4 * (row / VEC) + cc * 4) = v;
+        *reinterpret_cast<vec_t *>(tile + row * roww + (row / VEC) * skew + cc * 4) = v;
     }
     __syncthreads();
-    const int gpr = block / VEC;                           // 16-byte groups per Vt row
     E *out = Vt + (bh * T + j) * (size_t)d * block;
-    for (int c = threadIdx.x; c < roww * gpr; c += blockDim.x) {
-        const int w = c / gpr, kg = c % gpr;               // word column w of the rows kg*VEC .. kg*VEC+VEC-1
+    for (int c = threadIdx.x; c < roww * (block / VEC); c += blockDim.x) {
+        const int kgi = c % gpp, w = (c / gpp) % roww, gi = c / (gpp * roww);
+        const int kg = gi * gpp + kgi;                     // word column w of the rows kg*VEC .. kg*VEC+VEC-1
         uint32_t x[VEC];
 #pragma unroll
-        for (int u = 0; u < VEC; ++u) x[u] = tile[(kg * VEC + u) * roww + 4 * kg + w];
+        for (int u = 0; u < VEC; ++u) x[u] = tile[(kg * VEC + u) * roww + kg * skew + w];
+        E *og = out + (size_t)gi * d * G + kgi * VEC;      // feature e of this piece: og + e * G
         if (sizeof(E) == 4) {
             uintx4 v;
 #pragma unroll
             for (int u = 0; u < 4; ++u) v[u] = x[u];
-            *reinterpret_cast<uintx4 *>(out + (size_t)w * block + kg * VEC) = v;
+            *reinterpret_cast<uintx4 *>(og + (size_t)w * G) = v;
         } else {                                           // word w holds elements 2w (low half) and 2w + 1
             uintx4 lo, hi;
 #pragma unroll
@@ -140,8 +145,8 @@ __global__ __launch_bounds__(256) void gather_vt_kernel(const E *__restrict__ V,
                 lo[u] = __builtin_amdgcn_perm(x[(2 * u + 1) % VEC], x[(2 * u) % VEC], 0x05040100u);
                 hi[u] = __builtin_amdgcn_perm(x[(2 * u + 1) % VEC], x[(2 * u) % VEC], 0x07060302u);
             }
-            *reinterpret_cast<uintx4 *>(out + (size_t)(2 * w) * block + kg * VEC) = lo;
-            *reinterpret_cast<uintx4 *>(out + (size_t)(2 * w + 1) * block + kg * VEC) = hi;
+            *reinterpret_cast<uintx4 *>(og + (size_t)(2 * w) * G) = lo;
+            *reinterpret_cast<uintx4 *>(og + (size_t)(2 * w + 1) * G) = hi;
         }
     }
 }
@@ -203,11 +208,11 @@ extern "C" pbs_status pbs_segment_permute(const pbs_problem *p, const float *sco
                        (const uintx4 *)K, (const int32_t *)kidx, (uintx4 *)Kp, g.n, ilog2(cpr));
     if ((st = launch_status()) != PBS_OK) return st;
     if (p->dtype == PBS_BF16) {
-        const size_t lds = (size_t)g.block * g.d * 2 + (size_t)(g.block / 8) * 16;
+        const size_t lds = (size_t)g.block * g.d * 2 + (size_t)(g.block / 8) * (64 / (vt_group(g.block) / 8)) * 4;   // tile + skew
         hipLaunchKernelGGL(gather_vt_kernel<uint16_t>, dim3(g.T, nbh), dim3(256), lds, s, (const uint16_t *)V,
                            (const int32_t *)kidx, (uint16_t *)Vt, g.n, g.d, g.block, g.T);
     } else {
-        const size_t lds = (size_t)g.block * g.d * 4 + (size_t)(g.block / 4) * 16;
+        const size_t lds = (size_t)g.block * g.d * 4 + (size_t)(g.block / 4) * (64 / (vt_group(g.block) / 4)) * 4;
         hipLaunchKernelGGL(gather_vt_kernel<uint32_t>, dim3(g.T, nbh), dim3(256), lds, s, (const uint32_t *)V,
                            (const int32_t *)kidx, (uint32_t *)Vt, g.n, g.d, g.block, g.T);
     }

@@ -27,12 +27,13 @@ def i32_dev(a):
 
 
 def vt_layout(Vp, block):
-    """[B,H,N,d] (numpy) -> the library's block-transposed V' layout [B,H,T,d,block], zero padded."""
+    """[B,H,N,d] (numpy) -> the library's V' layout [B,H,T,block/G,d,G], G = min(block, 32), zero padded."""
     B, H, N, d = Vp.shape
     T = -(-N // block)
+    G = min(block, 32)
     pad = np.zeros((B, H, T * block, d), dtype=Vp.dtype)
     pad[:, :, :N] = Vp
-    return np.ascontiguousarray(pad.reshape(B, H, T, block, d).transpose(0, 1, 2, 4, 3))
+    return np.ascontiguousarray(pad.reshape(B, H, T, block // G, G, d).transpose(0, 1, 2, 3, 5, 4))
 
 
 def mask_from_bits(bits, T):
