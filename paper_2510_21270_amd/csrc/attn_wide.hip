@@ -198,16 +198,6 @@ __device__ __forceinline__ void s_mfma(floatx16 (&s)[2], const bf16x8 (&kf)[8], 
     }
 }
 
-// two probabilities: exp2(s * c2 - shift), packed; rsum += the rounded values
-__device__ __forceinline__ bf16x2 exp2_pack2(float s0, float s1, float c2, float shift, float &rsum)
-{
-    floatx2 pr = {__builtin_amdgcn_exp2f(__builtin_fmaf(s0, c2, -shift)), __builtin_amdgcn_exp2f(__builtin_fmaf(s1, c2, -shift))};
-    const bf16x2 t2 = __builtin_convertvector(pr, bf16x2);
-    const bf16x2 ones = {(bf16_t)1.0f, (bf16_t)1.0f};
-    rsum = __builtin_amdgcn_fdot2_f32_bf16(t2, ones, rsum, false);
-    return t2;
-}
-
 // What a sub-tile that is not plain needs before the softmax of one query tile: the token-level mask (masked scores
 // become -inf, i.e. probability 0), and for queries that meet their first visible key the reference, set to the row
 // maximum of this sub-tile.  A reference, once set, never moves (see the note on kBigRowSum), so O^T is never
@@ -263,14 +253,11 @@ __device__ __forceinline__ void step(State &st, floatx16 (&s_cur)[2], floatx16 (
     __builtin_amdgcn_sched_barrier(0);
     // Softmax of score pair q (query tile q / 8, scores 2 (q % 8) and + 1) in three stages, issued in consecutive
     // MFMA slots so that no instruction waits on the one just before it: multiply-add in slot 2 q, exponentials in
-    // slot 2 q + 1, rounding / row sum / pack in slot 2 q + 2.
-    float rsum[2] = {0.0f, 0.0f};
+    // slot 2 q + 1, rounding / row sum / pack in slot 2 q + 2.  The row sum adds the unrounded probabilities with two
+    // plain additions: on this chip the bf16 dot-product instruction that would sum the rounded pair in one go does
+    // not overlap with the matrix instructions the way ordinary vector arithmetic does.
+    floatx2 rsum[2] = {{0.0f, 0.0f}, {0.0f, 0.0f}};        // per query tile: sums over even and odd scores
     floatx2 pr = {0.0f, 0.0f}, ar = {0.0f, 0.0f};
-#ifdef PBS_PIN_DOT2
-#define PBS_PIN_RSUM(r) asm volatile("" : "+v"(r));
-#else
-#define PBS_PIN_RSUM(r)
-#endif
 #define PBS_SM_FMA(q)                                                                                        \
     {                                                                                                        \
         ar[0] = __builtin_fmaf(s_cur[(q) >> 3][2 * ((q) & 7)], c2, -st.mref[(q) >> 3]);                      \
@@ -285,9 +272,8 @@ __device__ __forceinline__ void step(State &st, floatx16 (&s_cur)[2], floatx16 (
     {                                                                                                        \
         bf16x2 t2 = __builtin_convertvector(pr, bf16x2);                                                     \
         asm volatile("" : "+v"(t2));                       /* the pack happens here, not where it is consumed */ \
-        const bf16x2 ones = {(bf16_t)1.0f, (bf16_t)1.0f};                                                    \
-        rsum[(q) >> 3] = __builtin_amdgcn_fdot2_f32_bf16(t2, ones, rsum[(q) >> 3], false);                   \
-        PBS_PIN_RSUM(rsum[(q) >> 3])                                                                         \
+        rsum[(q) >> 3] += pr;                                                                                \
+        asm volatile("" : "+v"(rsum[(q) >> 3]));                                                             \
         pf_new[(q) >> 3][((q) & 7) >> 2][2 * ((q) & 3)] = t2[0];                                             \
         pf_new[(q) >> 3][((q) & 7) >> 2][2 * ((q) & 3) + 1] = t2[1];                                         \
     }
@@ -380,10 +366,10 @@ __device__ __forceinline__ void step(State &st, floatx16 (&s_cur)[2], floatx16 (
 #undef PBS_SM_PACK
 #undef PBS_SM_EXP
 #undef PBS_SM_FMA
-#undef PBS_PIN_RSUM
-    st.l[0] += rsum[0];
-    st.l[1] += rsum[1];
-    st.bad = st.bad || !(rsum[0] <= kBigRowSum) || !(rsum[1] <= kBigRowSum);
+    const float rs0 = rsum[0][0] + rsum[0][1], rs1 = rsum[1][0] + rsum[1][1];
+    st.l[0] += rs0;
+    st.l[1] += rs1;
+    st.bad = st.bad || !(rs0 <= kBigRowSum) || !(rs1 <= kBigRowSum);
     __builtin_amdgcn_sched_barrier(0);
 }
 
