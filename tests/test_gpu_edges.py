@@ -213,3 +213,18 @@ print("narrow-only ok")
     env = dict(os.environ, PBS_ATTN_NARROW="1")
     out = subprocess.run([sys.executable, "-c", code], env=env, capture_output=True, text=True, timeout=240)
     assert out.returncode == 0 and "narrow-only ok" in out.stdout, out.stdout + out.stderr
+
+
+def test_matrix_rate_probe_runs_and_counts_its_work():
+    # measurement aid of bench.py: 512 workgroups x 2 waves x iters x 32 instructions of 32 x 32 x 16 multiply-adds
+    import ctypes
+    lib = pbs.load_library()
+    sink = torch.empty(65536, dtype=torch.float32, device="cuda")
+    flop = ctypes.c_double(0.0)
+    for random_operands in (0, 1):
+        assert lib.pbs_mfma_rate_probe(random_operands, 100, sink.data_ptr(), sink.numel(), ctypes.byref(flop), None) == 0
+        torch.cuda.synchronize()
+        assert flop.value == 512 * 2 * 100 * 32 * 2.0 * 32 * 32 * 16
+        assert torch.isfinite(sink).all()
+    assert (sink != 0).any()                           # random operands leave non-zero accumulators
+    assert pbs.mfma_rate_probe(True, iters=2000, reps=1) > 100.0
