@@ -51,6 +51,7 @@ typedef __attribute__((address_space(3))) void *lptr_t;
 struct __align__(16) Stage {
     unsigned char k[kStageB];
     unsigned char v[kStageB];
+    int pos[2 * KS];                                       // original positions of the keys in k (and of the next 32)
 };
 
 __device__ __forceinline__ int swap23(int m) { return (m & ~12) | ((m & 4) << 1) | ((m & 8) >> 1); }
@@ -120,12 +121,23 @@ __device__ __forceinline__ void issue_load(const StageLoad &a, const LaneOffsets
     __builtin_amdgcn_raw_ptr_buffer_load_lds(a.rsrc, (lptr_t)(a.dst + C * 1024), 16, off.dma[C], a.soff, 0, 0);
 }
 
+// Original positions of the 32 keys of part P of block j, next to their K' rows.  Only sub-tiles under the
+// token-level mask read them, but the load is issued for every sub-tile, by all lanes of both waves (four bytes per
+// lane, the same 256 bytes from each wave): one more instruction in the stream costs less than a branch around it.
 template <int P>
-__device__ __forceinline__ void issue_stage(Stage &sg, const TileBuffers &buf, const LaneOffsets &off, int j, int wave)
+__device__ __forceinline__ void issue_positions(Stage &sg, const TileBuffers &buf, int j, int lane)
+{
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(buf.pos, (lptr_t)sg.pos, 4, lane * 4, (j * BLOCK + P * KS) * 4, 0, 0);
+}
+
+template <int P>
+__device__ __forceinline__ void issue_stage(Stage &sg, const TileBuffers &buf, const LaneOffsets &off, int j, int wave,
+                                            int lane)
 {
     const StageLoad a = stage_load<P>(sg, buf, j, j, wave);
     issue_load<0>(a, off); issue_load<1>(a, off); issue_load<2>(a, off); issue_load<3>(a, off);
     issue_load<4>(a, off); issue_load<5>(a, off); issue_load<6>(a, off); issue_load<7>(a, off);
+    issue_positions<P>(sg, buf, j, lane);
 }
 
 // Every asynchronous load of this wave has landed, then all waves meet: the stages loaded so far are complete.
@@ -135,14 +147,14 @@ __device__ __forceinline__ void sync_stages()
     __syncthreads();
 }
 
-// The loop's meeting point.  Each wave has waited for all of its loads except the eight it issued in the previous
+// The loop's meeting point.  Each wave has waited for all of its loads except the nine it issued in the previous
 // iteration, and for its fragment reads; after the barrier the loads of every wave up to two iterations back are
 // complete.  That is all an iteration needs: it reads K' fragments loaded two iterations earlier and V'^T fragments
 // loaded four iterations earlier, so a load has two full iterations to arrive.  (A plain barrier instruction, not
 // __syncthreads(): the fence of the latter would wait for every load.)
 __device__ __forceinline__ void sync_older_stages()
 {
-    __builtin_amdgcn_s_waitcnt(0x0078);                    // vmcnt(8) lgkmcnt(0), gfx9 encoding
+    __builtin_amdgcn_s_waitcnt(0x0079);                    // vmcnt(9) lgkmcnt(0), gfx9 encoding
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
 }
@@ -202,17 +214,17 @@ __device__ __forceinline__ void s_mfma(floatx16 (&s)[2], const bf16x8 (&kf)[8], 
 // become -inf, i.e. probability 0), and for queries that meet their first visible key the reference, set to the row
 // maximum of this sub-tile.  A reference, once set, never moves (see the note on kBigRowSum), so O^T is never
 // rescaled and the softmax itself is the same code for every sub-tile.
-__device__ __forceinline__ void prepare_tile(State &st, int nt, floatx16 &s, __amdgpu_buffer_rsrc_t kpos, int slot0,
-                                             int room, bool masked, int qpos, float c2, int lh)
+__device__ __forceinline__ void prepare_tile(State &st, int nt, floatx16 &s, const int *kpos, int room, bool masked,
+                                             int qpos, float c2, int lh)
 {
     if (masked) {
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
             const int k8 = 16 * u + 8 * lh;                    // 8 consecutive keys of this lane
-            // original positions of the keys; a read past the end of the sequence returns 0 and is masked by lim
-            const uintx4 a = __builtin_amdgcn_raw_buffer_load_b128(kpos, k8 * 4, slot0 * 4, 0);
-            const uintx4 b = __builtin_amdgcn_raw_buffer_load_b128(kpos, k8 * 4 + 16, slot0 * 4, 0);
-            const int kp[8] = {(int)a[0], (int)a[1], (int)a[2], (int)a[3], (int)b[0], (int)b[1], (int)b[2], (int)b[3]};
+            // original positions of the keys; slots past the end of the sequence hold 0 and are masked by lim
+            const int4 a = *reinterpret_cast<const int4 *>(kpos + k8);
+            const int4 b = *reinterpret_cast<const int4 *>(kpos + k8 + 4);
+            const int kp[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
             const int lim = room - k8;                         // keys x >= lim of this group do not exist
 #pragma unroll
             for (int x = 0; x < 8; ++x)
@@ -236,19 +248,19 @@ __device__ __forceinline__ void prepare_tile(State &st, int nt, floatx16 &s, __a
 // pf_prev: probabilities of sub-tile t - 1 (from the previous iteration); pf_new: receives those of sub-tile t.
 // sg_v: stage P, whose V'^T part belongs to sub-tile t - 1; after the barrier it receives the K' part P of block jk
 // and the V'^T part (P + 3) % 4 of block jv.  sg_k: stage (P + 2) % 4, K' fragments of sub-tile t + 2.
-// slot0 / room / masked describe sub-tile t.
+// room / masked describe sub-tile t (its key positions are in sg_v.pos).
 template <int P>
 __device__ __forceinline__ void step(State &st, floatx16 (&s_cur)[2], floatx16 (&s_nxt)[2], bf16x8 (&kf)[8],
                                      const bf16x8 (&qf)[2][8], const bf16x8 (&pf_prev)[2][2], bf16x8 (&pf_new)[2][2],
-                                     Stage &sg_v, const Stage &sg_k, const int (&qpos)[2], int slot0, int room,
-                                     bool masked, float c2, int lh, const TileBuffers &buf, const LaneOffsets &off,
-                                     int jk, int jv, int wave)
+                                     Stage &sg_v, const Stage &sg_k, const int (&qpos)[2], int room, bool masked,
+                                     float c2, int lh, const TileBuffers &buf, const LaneOffsets &off, int jk, int jv,
+                                     int wave, int lane)
 {
     bf16x8 vf[8];
     if (masked || !__all(st.seen[0] && st.seen[1])) {
         asm volatile("" ::: "memory");                     // keeps this rare block out of the straight-line code
-        prepare_tile(st, 0, s_cur[0], buf.pos, slot0, room, masked, qpos[0], c2, lh);
-        prepare_tile(st, 1, s_cur[1], buf.pos, slot0, room, masked, qpos[1], c2, lh);
+        prepare_tile(st, 0, s_cur[0], sg_v.pos, room, masked, qpos[0], c2, lh);
+        prepare_tile(st, 1, s_cur[1], sg_v.pos, room, masked, qpos[1], c2, lh);
     }
     __builtin_amdgcn_sched_barrier(0);
     // Softmax of score pair q (query tile q / 8, scores 2 (q % 8) and + 1) in three stages, issued in consecutive
@@ -353,6 +365,7 @@ __device__ __forceinline__ void step(State &st, floatx16 (&s_cur)[2], floatx16 (
         PBS_SM_SLOT(16 + (n))                                                                                \
     }
     PBS_PLD_SLOT(0) PBS_PLD_SLOT(1) PBS_PLD_SLOT(2) PBS_PLD_SLOT(3)
+    issue_positions<P>(sg_v, buf, jk, lane);
     PBS_KF_SLOT(4) PBS_KF_SLOT(5) PBS_KF_SLOT(6) PBS_KF_SLOT(7)
     PBS_PV_SLOT(8) PBS_PV_SLOT(9) PBS_PV_SLOT(10) PBS_PV_SLOT(11) PBS_PV_SLOT(12) PBS_PV_SLOT(13) PBS_PV_SLOT(14)
     PBS_PV_SLOT(15)
@@ -469,10 +482,10 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         // prologue: the four parts of the first block, its first scores, the K' fragments of part 1
         int jraw = entry(0);
         int jc = jraw < 0 ? 0 : jraw;
-        issue_stage<0>(sg0, buf, off, jc, wave);
-        issue_stage<1>(sg1, buf, off, jc, wave);
-        issue_stage<2>(sg2, buf, off, jc, wave);
-        issue_stage<3>(sg3, buf, off, jc, wave);
+        issue_stage<0>(sg0, buf, off, jc, wave, lane);
+        issue_stage<1>(sg1, buf, off, jc, wave, lane);
+        issue_stage<2>(sg2, buf, off, jc, wave, lane);
+        issue_stage<3>(sg3, buf, off, jc, wave, lane);
         sync_stages();
         floatx16 sa[2], sb[2];
         bf16x8 kf[8];
@@ -493,15 +506,14 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
             const int jn = jnraw < 0 ? 0 : jnraw;
             const bool masked = jraw < 0 || jraw >= jmask;
             const int room0 = jraw < 0 ? 0 : g.n - jraw * BLOCK;   // keys of the block that exist
-            const int slot0 = jc * BLOCK;                          // first key slot of the block
             // part p: probabilities of part p; scores of part p + 1; O^T update with part p - 1; K' fragments of
             // part p + 2 (parts outside 0..3 are those of the neighbouring listed blocks).  Stage p is refilled with
             // K' part p of the next block and V'^T part p - 1 of the next block (part 3 of this block when p = 0).
             // The first iteration of a chunk updates O^T with zero probabilities.
-            step<0>(st, sa, sb, kf, qf, pa, pb, sg0, sg2, qpos, slot0, room0, masked, c2, lh, buf, off, jn, jc, wave);
-            step<1>(st, sb, sa, kf, qf, pb, pa, sg1, sg3, qpos, slot0 + KS, room0 - KS, masked, c2, lh, buf, off, jn, jn, wave);
-            step<2>(st, sa, sb, kf, qf, pa, pb, sg2, sg0, qpos, slot0 + 2 * KS, room0 - 2 * KS, masked, c2, lh, buf, off, jn, jn, wave);
-            step<3>(st, sb, sa, kf, qf, pb, pa, sg3, sg1, qpos, slot0 + 3 * KS, room0 - 3 * KS, masked, c2, lh, buf, off, jn, jn, wave);
+            step<0>(st, sa, sb, kf, qf, pa, pb, sg0, sg2, qpos, room0, masked, c2, lh, buf, off, jn, jc, wave, lane);
+            step<1>(st, sb, sa, kf, qf, pb, pa, sg1, sg3, qpos, room0 - KS, masked, c2, lh, buf, off, jn, jn, wave, lane);
+            step<2>(st, sa, sb, kf, qf, pa, pb, sg2, sg0, qpos, room0 - 2 * KS, masked, c2, lh, buf, off, jn, jn, wave, lane);
+            step<3>(st, sb, sa, kf, qf, pb, pa, sg3, sg1, qpos, room0 - 3 * KS, masked, c2, lh, buf, off, jn, jn, wave, lane);
             jraw = jnraw;
             jc = jn;
         }
