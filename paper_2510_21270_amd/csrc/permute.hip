@@ -69,23 +69,39 @@ __global__ __launch_bounds__(256) void move_rows_kernel(const uintx4 *__restrict
                                                         const int32_t *__restrict__ idx,
                                                         uintx4 *__restrict__ dst, int n, int cpr_log2)
 {
-    // grid = (x, nbh): blockIdx.y is the head, x strides over that head's n * cpr chunks
+    // grid = (x, nbh): blockIdx.y is the head; workgroup x owns a contiguous range of that head's n * cpr chunks and
+    // moves it in batches of U x 256 chunks: all index loads of a batch, then all data loads, then all stores, so
+    // that every thread keeps U independent 16-byte loads in flight.
+    constexpr int U = 4;
     const size_t head = (size_t)blockIdx.y * n;
     const uint32_t chunks = (uint32_t)n << cpr_log2;
     const uint32_t cmask = (1u << cpr_log2) - 1u;
     const uintx4 *hsrc = src + (head << cpr_log2);
     uintx4 *hdst = dst + (head << cpr_log2);
     const int32_t *hidx = idx ? idx + head : nullptr;
-    for (uint32_t c = blockIdx.x * blockDim.x + threadIdx.x; c < chunks; c += gridDim.x * blockDim.x) {
-        const uint32_t row = c >> cpr_log2, cc = c & cmask;
-        const int32_t other = hidx ? hidx[row] : (int32_t)row;
-        const bool ok = other >= 0 && other < n;
-        if (SCATTER) {
-            if (ok) hdst[((uint32_t)other << cpr_log2) + cc] = hsrc[c];
-        } else {
-            uintx4 v = {0u, 0u, 0u, 0u};
-            if (ok) v = hsrc[((uint32_t)other << cpr_log2) + cc];
-            hdst[c] = v;
+    const uint32_t batch = U * 256;
+    const uint32_t per = ((chunks + gridDim.x - 1) / gridDim.x + batch - 1) / batch * batch;
+    const uint32_t begin = min(blockIdx.x * per, chunks), end = min(begin + per, chunks);
+    for (uint32_t c0 = begin + threadIdx.x; c0 < end; c0 += batch) {
+        int32_t other[U];
+        uintx4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t c = c0 + u * 256;
+            other[u] = c < end ? (hidx ? hidx[c >> cpr_log2] : (int32_t)(c >> cpr_log2)) : -1;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t c = c0 + u * 256;
+            const bool ok = other[u] >= 0 && other[u] < n;
+            v[u] = uintx4{0u, 0u, 0u, 0u};
+            if (SCATTER ? c < end : ok) v[u] = hsrc[SCATTER ? c : ((uint32_t)other[u] << cpr_log2) + (c & cmask)];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t c = c0 + u * 256;
+            const bool ok = other[u] >= 0 && other[u] < n;
+            if (SCATTER ? ok : c < end) hdst[SCATTER ? ((uint32_t)other[u] << cpr_log2) + (c & cmask) : c] = v[u];
         }
     }
 }
@@ -114,15 +130,31 @@ __global__ __launch_bounds__(256) void gather_vt_kernel(const E *__restrict__ V,
     const int gpp = G / VEC;                               // 16-byte pieces per Vt row
     const int skew = 64 / gpp;                             // words; gpp is 2, 4 or 8
     typedef E vec_t __attribute__((ext_vector_type(VEC)));
-    for (int c = threadIdx.x; c < block * cpr; c += blockDim.x) {
-        const int row = c / cpr, cc = c % cpr;
-        const int slot = j * block + row;
-        vec_t v = {};
-        if (slot < n) {
-            const int32_t src = kidx ? kidx[bh * n + slot] : slot;
-            if (src >= 0 && src < n) v = *reinterpret_cast<const vec_t *>(V + (bh * n + src) * (size_t)d + cc * VEC);
+    // batches of U chunks per thread: index loads, then row loads, then the LDS stores
+    constexpr int U = 4;
+    const int total = block * cpr;
+    for (int c0 = threadIdx.x; c0 < total; c0 += U * 256) {
+        int32_t from[U];
+        vec_t v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int c = c0 + u * 256;
+            const int slot = j * block + c / cpr;
+            from[u] = (c < total && slot < n) ? (kidx ? kidx[bh * n + slot] : slot) : -1;
         }
-        *reinterpret_cast<vec_t *>(tile + row * roww + (row / VEC) * skew + cc * 4) = v;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int c = c0 + u * 256;
+            v[u] = vec_t{};
+            if (from[u] >= 0 && from[u] < n)
+                v[u] = *reinterpret_cast<const vec_t *>(V + (bh * n + from[u]) * (size_t)d + (c % cpr) * VEC);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int c = c0 + u * 256;
+            const int row = c / cpr;
+            if (c < total) *reinterpret_cast<vec_t *>(tile + row * roww + (row / VEC) * skew + (c % cpr) * 4) = v[u];
+        }
     }
     __syncthreads();
     E *out = Vt + (bh * T + j) * (size_t)d * block;
