@@ -5,17 +5,19 @@
 // one wave runs per SIMD, and the softmax reference of a query is fixed at its first visible key (see kBigRowSum):
 //   * every K' / V'^T fragment read from LDS feeds two MFMAs instead of one;
 //   * the softmax arithmetic of a wave is interleaved, in its own instruction stream, with independent MFMAs (the
-//     scores of the NEXT sub-tile, the O^T update of the other query tile), so the matrix pipe does not depend on a
+//     scores of the NEXT sub-tile, the O^T update with the PREVIOUS one), so the matrix pipe does not depend on a
 //     second wave happening to be in the opposite phase.
 // Key blocks are consumed in sub-tiles of 32 keys.  Sub-tile u of a list chunk covers keys [32 p, 32 p + 32),
 // p = u % 4, of listed block u / 4.  A wave has a single instruction stream to itself, so the loop is a three-deep
 // software pipeline in which no MFMA of an iteration depends on the vector arithmetic of the same iteration, and that
 // arithmetic is spread evenly over the iteration's 32 MFMAs.  Iteration t:
-//     MFMAs  0..15:  S(t + 1) = K'(t + 1) Q'^T, both query tiles          || V'^T fragment reads of sub-tile t - 1
-//     MFMAs 16..31:  O^T += V'^T(t - 1) P^T(t - 1), both query tiles      || K' fragment reads of sub-tile t + 2,
-//                    barrier (every load issued so far has landed; the stage read above is free), then the loads
-//                    of K'(t + 4) and V'^T(t + 3), one per MFMA
+//     MFMAs  0..15:  S(t + 1) = K'(t + 1) Q'^T, both query tiles
+//     MFMAs 16..31:  O^T += V'^T(t - 1) P^T(t - 1), both query tiles
 //     all along:     P^T(t) = softmax arithmetic on S(t), one score pair per two MFMAs
+//     LDS traffic:   V'^T(t - 1) fragment reads under MFMAs 0..7; after MFMA 11 the waves meet (every load issued
+//                    two or more iterations ago has landed, the V'^T part just read is free); the loads of K'(t + 4),
+//                    V'^T(t + 3) and the key positions of sub-tile t + 4 go out under MFMAs 12..20; K'(t + 2)
+//                    fragment reads under MFMAs 16..23
 // LDS holds a 4-deep ring of stages filled by asynchronous buffer->LDS loads; stage p holds the K' part p and the
 // V'^T part (p + 3) % 4 of their blocks, which is what iteration t = p (mod 4) frees and refills.
 // A sub-tile that is not plain (token-level mask, queries without a visible key so far) first rewrites its scores
