@@ -109,6 +109,9 @@ def main():
     ap.add_argument("--no-permute", action="store_true",
                     help="keep the keys in token order (identity permutation): what Algorithm 2 selects, and what "
                          "the attention costs, without the paper's permutation")
+    ap.add_argument("--coverage", action="store_true",
+                    help="after the timed region, also report the true attention mass inside the selected blocks "
+                         "(two more attention passes, one of them over every admitted block)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="after the timed region, run one plain device copy of known size through pbs_unpermute, so "
                          "that a rocprofv3 --pmc run of this command shows what FETCH_SIZE / WRITE_SIZE read for it")
@@ -215,6 +218,12 @@ def main():
         extras["plain_copy"] = {"ms": ms_copy, "GBps": nbytes / ms_copy / 1e6, "bytes": nbytes}
         extras["unpermute_random_sigma"] = {"ms": ms_sigma, "GBps": (nbytes + sigma.numel() * 4) / ms_sigma / 1e6}
         del scratch, sigma
+        if args.coverage and not given:
+            # true attention mass inside the selected blocks (two more attention passes, untimed)
+            cov = pbs.coverage(p, Q, pipe.Kp, pipe.Vt, None, pipe.kidx, pipe.row_cnt, pipe.col_idx, ws=pipe.ws4)
+            extras["attention_mass_covered"] = {"mean": float(cov.mean()), "min_row": float(cov.min()),
+                                                "rows_below_tau": float((cov < w.tau).float().mean())}
+            del cov
         # what the matrix units sustain on their own, with operand bits that cost no / realistic switching power
         extras["mfma_alone_tflops"] = {"zero_operands": pbs.mfma_rate_probe(False),
                                        "random_operands": pbs.mfma_rate_probe(True)}

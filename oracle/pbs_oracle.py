@@ -184,6 +184,33 @@ def attn_rows(Qp, Kp, Vp, qidx, kidx, row_cnt, col_idx, block, rows, scale=0.0, 
     return (out, lse) if want_lse else out
 
 
+def all_allowed_lists(B, Hq, N, block, segment):
+    """Block lists that name every key block the extended causal mask C admits (Section "Segmented Permutation
+    for Causal Attention"): the whole own segment for query blocks of full segments, blocks 0..i in the tail."""
+    T = -(-N // block)
+    R, G = segment // block, N // segment
+    i = np.arange(T)
+    s = i // R
+    allowed = np.where(s < G, np.minimum((s + 1) * R, T), i + 1).astype(np.int32)
+    row_cnt = np.broadcast_to(allowed, (B, Hq, T)).copy()
+    col_idx = np.broadcast_to(np.arange(T, dtype=np.int32), (B, Hq, T, T)).copy()
+    return row_cnt, col_idx
+
+
+def coverage(Qp, Kp, qidx, kidx, row_cnt, col_idx, block, segment, scale=0.0):
+    """Attention mass captured by the listed blocks, per query slot [B,Hq,N]: the inner sums of the block-selection
+    objective (Section "The Problem of Information Fragmentation"), with A the softmax over every visible key.
+    Written as exp(lse over the listed blocks - lse over all admitted blocks)."""
+    B, Hq, N, d = Qp.shape
+    Vz = np.zeros_like(np.asarray(Kp, dtype=np.float32))
+    _, lse_sel = attn_fwd(Qp, Kp, Vz, qidx, kidx, row_cnt, col_idx, block, scale, want_lse=True)
+    rc_all, ci_all = all_allowed_lists(B, Hq, N, block, segment)
+    _, lse_all = attn_fwd(Qp, Kp, Vz, qidx, kidx, rc_all, ci_all, block, scale, want_lse=True)
+    with np.errstate(invalid="ignore"):
+        cov = np.exp(lse_sel - lse_all)
+    return np.where(np.isfinite(lse_sel), cov, 0.0)
+
+
 def dense_causal(Q, K, V, scale=0.0):
     """Dense causal attention in the original token order -> O [B,Hq,N,d] float64."""
     B, Hq, N, d = Q.shape

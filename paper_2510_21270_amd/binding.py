@@ -179,6 +179,30 @@ def unpermute(p, Op, qidx, O=None):
     return O
 
 
+def all_allowed_lists(p, device="cuda"):
+    """row_cnt, col_idx naming every key block the extended causal mask admits (what a dense causal pass visits)."""
+    T = T_of(p)
+    R, G = p.segment // p.block, p.n // p.segment
+    i = torch.arange(T, device=device)
+    s = i // R
+    allowed = torch.where(s < G, torch.clamp((s + 1) * R, max=T), i + 1).to(torch.int32)
+    row_cnt = allowed.view(1, 1, T).expand(p.batch, p.h_q, T).contiguous()
+    col_idx = torch.arange(T, device=device, dtype=torch.int32).view(1, 1, 1, T).expand(p.batch, p.h_q, T, T).contiguous()
+    return row_cnt, col_idx
+
+
+def coverage(p, Qp, Kp, Vt, qidx, kidx, row_cnt, col_idx, ws=None):
+    """Attention mass that the listed blocks capture, per query slot [batch, h_q, n] (float32): the inner sums of the
+    block-selection objective in Section "The Problem of Information Fragmentation", A being the softmax over every
+    visible key.  Two pbs_attn_fwd calls: exp(lse over the listed blocks - lse over all admitted blocks)."""
+    Op = torch.empty_like(Qp)
+    _, lse_sel = attn_fwd(p, Qp, Kp, Vt, qidx, kidx, row_cnt, col_idx, Op, want_lse=True, ws=ws)
+    rc_all, ci_all = all_allowed_lists(p, Qp.device)
+    _, lse_all = attn_fwd(p, Qp, Kp, Vt, qidx, kidx, rc_all, ci_all, Op, want_lse=True, ws=ws)
+    cov = torch.exp(lse_sel - lse_all)
+    return torch.where(torch.isfinite(lse_sel), cov, torch.zeros_like(cov))
+
+
 def mfma_rate_probe(random_operands, iters=20000, reps=3):
     """TFLOP/s of the matrix units alone (best of `reps` launches timed with events on the current stream)."""
     sink = torch.empty(65536, dtype=torch.float32, device="cuda")

@@ -134,6 +134,25 @@ def test_attn_fwd_and_unpermute(lib, oracle, name, sigma):
     np.testing.assert_allclose(lse.cpu().numpy(), res["lse"], rtol=0, atol=2e-2 if w.dtype == "bf16" else 1e-4)
 
 
+@pytest.mark.parametrize("sigma", [False, True])
+@pytest.mark.parametrize("name", ["c1", "bf16_b128", "bf16_b64", "bf16_r7"])
+def test_coverage_of_the_selected_blocks(lib, oracle, name, sigma):
+    # attention mass captured by the mask (two pbs_attn_fwd calls: listed blocks, all admitted blocks)
+    w, res = _oracle_run(oracle, name, sigma)
+    p = make_problem(w)
+    qidx = i32_dev(res["qidx"]) if sigma else None
+    got = pbs.coverage(p, to_dev(res["Qp"], w.dtype), to_dev(res["Kp"], w.dtype),
+                       to_dev(vt_layout(res["Vp"], w.block), w.dtype), qidx, i32_dev(res["kidx"]),
+                       i32_dev(res["row_cnt"]), i32_dev(res["col_idx"]))
+    torch.cuda.synchronize()
+    want = oracle.coverage(res["Qp"], res["Kp"], res["qidx"], res["kidx"], res["row_cnt"], res["col_idx"], w.block,
+                           w.segment)
+    got = got.cpu().numpy()
+    assert got.min() >= 0.0 and got.max() <= 1.0 + 1e-3
+    np.testing.assert_allclose(got, want, rtol=0, atol=5e-3 if w.dtype == "bf16" else 1e-4)
+    assert want.mean() > 0.5                            # tau >= 0.7 on pooled scores keeps most of the true mass here
+
+
 @pytest.mark.parametrize("name", CASES)
 def test_pipeline_composed(lib, oracle, name):
     """All five stages chained on the GPU.  GPU scores are only close to the oracle's, so near-tied keys may swap

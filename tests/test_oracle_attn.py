@@ -145,3 +145,43 @@ def test_pipeline_mass_report_on_tiny_config(oracle):
     assert res["mask"].shape == (1, 2, 8, 8)
     assert (res["row_cnt"] >= 1).all()
     np.testing.assert_allclose(res["s"].sum(-1), 1.0, rtol=1e-12)
+
+
+def test_coverage_equals_brute_force_attention_mass(oracle):
+    # coverage of a block list = sum of the true attention probabilities (softmax over every visible key, in the
+    # original token order) that fall into listed blocks of the permuted layout; brute force on a tiny case
+    B, Hq, Hkv, N, d, block, segment = 1, 2, 1, 100, 16, 16, 32
+    rng = np.random.default_rng(5)
+    Q = rng.standard_normal((B, Hq, N, d)).astype(np.float32)
+    K = rng.standard_normal((B, Hkv, N, d)).astype(np.float32)
+    kidx = wl.random_segment_perm(9, B * Hkv, N, segment).reshape(B, Hkv, N)
+    Kp = oracle.gather_rows(K, kidx)
+    T = -(-N // block)
+    # a random list per query block, inside what the extended causal mask admits, diagonal always on
+    rc_all, ci_all = oracle.all_allowed_lists(B, Hq, N, block, segment)
+    row_cnt = np.zeros((B, Hq, T), dtype=np.int32)
+    col_idx = np.full((B, Hq, T, T), -1, dtype=np.int32)
+    sel = np.zeros((B, Hq, T, T), dtype=bool)
+    for h in range(Hq):
+        for i in range(T):
+            keep = rng.random(rc_all[0, h, i]) < 0.5
+            keep[min(i, rc_all[0, h, i] - 1)] = True
+            cols = np.nonzero(keep)[0]
+            row_cnt[0, h, i] = len(cols)
+            col_idx[0, h, i, :len(cols)] = cols
+            sel[0, h, i, cols] = True
+    got = oracle.coverage(Q, Kp, None, kidx, row_cnt, col_idx, block, segment)
+    # brute force: A in token order; key token t sits in permuted slot slot_of[t], i.e. in block slot_of[t] // block
+    slot_of = np.empty(N, dtype=np.int64)
+    slot_of[kidx[0, 0]] = np.arange(N)
+    for h in range(Hq):
+        L = Q[0, h].astype(np.float64) @ K[0, 0].astype(np.float64).T / math.sqrt(d)
+        L[np.triu_indices(N, k=1)] = -np.inf
+        A = softmax(L, axis=1)
+        for q in range(N):
+            inside = sel[0, h, q // block, slot_of // block]            # per key token: is its block listed
+            want = A[q, inside].sum()
+            assert abs(got[0, h, q] - want) < 1e-12, (h, q)
+    # listing everything captures all of it
+    full = oracle.coverage(Q, Kp, None, kidx, rc_all, ci_all, block, segment)
+    np.testing.assert_allclose(full, 1.0, rtol=0, atol=1e-12)
