@@ -109,6 +109,10 @@ def main():
     ap.add_argument("--no-permute", action="store_true",
                     help="keep the keys in token order (identity permutation): what Algorithm 2 selects, and what "
                          "the attention costs, without the paper's permutation")
+    ap.add_argument("--replicate-kv", action="store_true",
+                    help="give every query head its own copy of its group's K and V (h_kv = h_q), i.e. one key "
+                         "permutation per query head instead of one per kv head (appendix 'GQA Handling'); a "
+                         "different configuration, named so in config.workload")
     ap.add_argument("--coverage", action="store_true",
                     help="after the timed region, also report the true attention mass inside the selected blocks "
                          "(two more attention passes, one of them over every admitted block)")
@@ -128,6 +132,11 @@ def main():
     t_gen = time.perf_counter()
     w = make_workload(args.workload)
     t_gen = time.perf_counter() - t_gen
+    if args.replicate_kv and w.h_kv != w.h_q:
+        r = w.h_q // w.h_kv
+        w.K, w.V = np.repeat(w.K, r, axis=1), np.repeat(w.V, r, axis=1)
+        w.extra = {k: v for k, v in w.extra.items() if k != "planted"}      # keyed by kv head
+        w.h_kv, w.name = w.h_q, w.name + "_replicated_kv"
     p = pbs.problem(w.batch, w.h_q, w.h_kv, w.n, w.d, w.block, w.segment, w.dtype, tau=w.tau, flags=w.flags)
     Q, K, V = to_dev(w.Q, w.dtype), to_dev(w.K, w.dtype), to_dev(w.V, w.dtype)
     pipe = pbs.Pipeline(p)
