@@ -247,3 +247,21 @@ class Pipeline:
         block_mask(p, Qp, self.Kp, self.mask_bits, self.row_cnt, self.col_idx, self.ws3)
         attn_fwd(p, Qp, self.Kp, self.Vt, qidx, self.kidx, self.row_cnt, self.col_idx, self.Op, ws=self.ws4)
         return unpermute(p, self.Op, qidx, self.O)
+
+    def capture(self, Q, K, V, qidx=None):
+        """Record the pipeline into a HIP graph that reads these very tensors (refill them in place, then replay()).
+        The library allocates nothing, never synchronises and records no memset nodes, so the calls can be captured
+        as they are; short sequences, where the dozen launches cost more than the kernels, gain from it."""
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            self.run(Q, K, V, qidx)                        # everything lazily initialised happens outside the capture
+        torch.cuda.current_stream().wait_stream(side)
+        self.graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(self.graph):
+            self._graph_out = self.run(Q, K, V, qidx)
+        return self._graph_out
+
+    def replay(self):
+        self.graph.replay()
+        return self._graph_out
