@@ -118,3 +118,14 @@ def test_paper_memory_figures():
     # d=128, N=128K, are both about 32 MiB per head.
     assert 128 * 131072 * 2 == 32 * 2 ** 20
     assert 131072 * 128 * 2 == 32 * 2 ** 20
+
+
+def test_bench_refuses_more_than_one_gpu():
+    # every box of this build has one GPU; the bench must say so instead of starting ranks
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                         timeout=120)
+    assert res.returncode != 0
+    assert "one GPU" in (res.stderr + res.stdout)
