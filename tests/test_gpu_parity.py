@@ -200,3 +200,56 @@ def test_determinism(lib, oracle):
     torch.cuda.synchronize()
     assert torch.equal(o1, o2) and torch.equal(s1, pipe.scores) and torch.equal(k1, pipe.kidx)
     assert torch.equal(m1, pipe.mask_bits)
+
+
+def _random_shape(seed, wide):
+    """A seeded random problem: the matrix-core path for block 128 (wide) or any supported combination."""
+    rng = np.random.default_rng(1000 + seed)
+    if wide:
+        dtype, d, block = "bf16", 128, 128
+        segment = int(rng.choice([128, 256, 512, 1024]))
+        n = int(rng.integers(1, 2600))
+    else:
+        dtype = str(rng.choice(["bf16", "f32"]))
+        d = int(rng.choice([64, 128]))
+        block = int(rng.choice([16, 32, 64, 128]))
+        segment = block * int(rng.choice([1, 2, 4, 8]))
+        n = int(rng.integers(1, 900))
+    h_kv = int(rng.choice([1, 2, 3]))
+    h_q = h_kv * int(rng.choice([1, 2, 4]))
+    tau = float(rng.choice([0.3, 0.6, 0.9, 0.99]))
+    flags = int(rng.integers(0, 2))
+    return wl.planted("rnd%d" % seed, 500 + seed, h_q, h_kv, n, d, block, segment, tau, dtype, 4,
+                      rope_base=5e5 if seed % 2 else None, flags=flags)
+
+
+@pytest.mark.parametrize("wide", [True, False])
+@pytest.mark.parametrize("seed", range(10))
+def test_random_shapes_stage_by_stage(lib, oracle, seed, wide):
+    # every stage on the oracle's output of the stage before, for shapes no other test names
+    w = _random_shape(seed, wide)
+    sigma = seed % 3 == 0
+    qidx = wl.random_segment_perm(seed, w.batch * w.h_q, w.n, w.segment).reshape(w.batch, w.h_q, w.n) if sigma else None
+    res = oracle.pipeline(w.Q, w.K, w.V, w.block, w.segment, w.tau, flags=w.flags, qidx=qidx)
+    p = make_problem(w)
+    what = "%s n=%d hq=%d hkv=%d d=%d block=%d segment=%d tau=%g flags=%d sigma=%s" % (
+        w.dtype, w.n, w.h_q, w.h_kv, w.d, w.block, w.segment, w.tau, w.flags, sigma)
+    s = pbs.key_scores(p, to_dev(w.Q, w.dtype), to_dev(w.K, w.dtype)).cpu().numpy().astype(np.float64)
+    np.testing.assert_allclose(s, res["s"], rtol=2e-3 if (w.dtype == "bf16" and w.d == 128) else 1e-5, atol=1e-37,
+                               err_msg=what)
+    kidx, Kp, Vt = pbs.segment_permute(p, torch.from_numpy(res["s_handoff"]).cuda(), to_dev(w.K, w.dtype),
+                                       to_dev(w.V, w.dtype))
+    np.testing.assert_array_equal(kidx.cpu().numpy(), res["kidx"], err_msg=what)
+    np.testing.assert_array_equal(to_host(Kp), res["Kp"].astype(np.float64), err_msg=what)
+    np.testing.assert_array_equal(to_host(Vt), vt_layout(res["Vp"], w.block).astype(np.float64), err_msg=what)
+    bits, cnt, cols = pbs.block_mask(p, to_dev(res["Qp"], w.dtype), Kp)
+    np.testing.assert_array_equal(mask_from_bits(bits, w.T), res["mask"], err_msg=what)
+    np.testing.assert_array_equal(cnt.cpu().numpy(), res["row_cnt"], err_msg=what)
+    qd = i32_dev(qidx) if sigma else None
+    Op, lse = pbs.attn_fwd(p, to_dev(res["Qp"], w.dtype), Kp, Vt, qd, kidx, cnt, cols, want_lse=True)
+    O = pbs.unpermute(p, Op, qd)
+    torch.cuda.synchronize()
+    check_close(to_host(Op), res["Op"], w.dtype, what + " O'")
+    check_close(to_host(O), res["O"], w.dtype, what + " O")
+    np.testing.assert_allclose(lse.cpu().numpy(), res["lse"], rtol=0, atol=2e-2 if w.dtype == "bf16" else 1e-4,
+                               err_msg=what)
