@@ -118,3 +118,32 @@ def test_full_size_given_lists_on_sampled_rows(oracle, rho):
         check_close(to_host(Op[b, h, sl]), want[u], "bf16", "c5 rho=%g row (%d,%d,%d)" % (rho, b, h, i))
         np.testing.assert_allclose(lse[b, h, sl].cpu().numpy(), want_lse[u], rtol=0, atol=2e-2)
     assert torch.isfinite(Op).all()
+
+
+def test_maximum_length_dense_equals_causal_attention_on_sampled_blocks():
+    # the largest supported length (T = 4096 blocks): tau > 1 keeps every admitted block, so whatever the scores made
+    # of the key order, the pipeline must reproduce dense causal attention (Theorem 1).  Sampled query blocks are
+    # compared with fp32 matrix products of the very same bf16 inputs; no oracle run fits this size.
+    N, Hq, Hkv, d, B, S = 524288, 4, 1, 128, 128, 1024
+    gen = torch.Generator(device="cuda").manual_seed(11)
+    Q = torch.randn(1, Hq, N, d, device="cuda", generator=gen).to(torch.bfloat16)
+    K = torch.randn(1, Hkv, N, d, device="cuda", generator=gen).to(torch.bfloat16)
+    V = torch.randn(1, Hkv, N, d, device="cuda", generator=gen).to(torch.bfloat16)
+    p = pbs.problem(1, Hq, Hkv, N, d, B, S, "bf16", tau=1.5)
+    pipe = pbs.Pipeline(p)
+    O = pipe.run(Q, K, V)
+    torch.cuda.synchronize()
+    T = N // B
+    assert int(pipe.row_cnt.sum()) == Hq * (S // B) ** 2 * (N // S) * (N // S + 1) // 2     # R^2 G (G + 1) / 2 per head
+    seg = torch.arange(N, device="cuda") // S
+    assert torch.equal(pipe.kidx[0, 0].long() // S, seg)                  # every key stays in its segment
+    for (h, i) in [(0, 0), (1, 1), (2, T // 2 + 3), (3, T - 1), (0, T - 8)]:
+        q = Q[0, h, i * B:(i + 1) * B].float()
+        k = K[0, 0, :(i + 1) * B].float()
+        v = V[0, 0, :(i + 1) * B].float()
+        L = (q @ k.T) / d ** 0.5
+        pos_q = torch.arange(i * B, (i + 1) * B, device="cuda")[:, None]
+        pos_k = torch.arange((i + 1) * B, device="cuda")[None, :]
+        ref = torch.softmax(L.masked_fill(pos_k > pos_q, float("-inf")), dim=1) @ v
+        err = (O[0, h, i * B:(i + 1) * B].float() - ref).abs()
+        assert float(err.max()) <= 2e-2 and float(err.mean()) <= 2e-3, (h, i, float(err.max()), float(err.mean()))
