@@ -29,7 +29,8 @@ __device__ inline int swap23(int m) { return (m & ~12) | ((m & 4) << 1) | ((m & 
 
 // ---------------------------------------------------------------------------------------------
 // MFMA kernel.  BLOCK = block size; WAVES = waves per workgroup; each wave owns BLOCK / WAVES query rows.
-// Key blocks are consumed in sub-tiles of KT = 64 keys.  K' and V'^T sub-tiles are double-buffered in LDS and
+// Key blocks are consumed in sub-tiles of KT keys (64 for block 128; 32 for block 64, whose two-wave workgroups then
+// need 39 KB of LDS, so that four of them -- two waves per SIMD -- share a CU).  K' and V'^T sub-tiles are double-buffered in LDS and
 // filled by asynchronous buffer->LDS loads (no registers, no LDS store instructions): while sub-tile s is being
 // multiplied, sub-tile s+1 is in flight.  One barrier per sub-tile.
 // grid = 1-D, see the workgroup decoding at the top of the kernel.
@@ -41,8 +42,7 @@ __device__ inline int swap23(int m) { return (m & ~12) | ((m & 4) << 1) | ((m & 
 // mask, and a query that has not met a visible key yet take the exact path (row maximum, reference update,
 // rescale of O and l).
 // ---------------------------------------------------------------------------------------------
-constexpr int KT = 64;                                     // keys per sub-tile
-constexpr int kListChunk = 1024;                           // listed blocks staged in LDS at a time
+constexpr int kListChunk = 256;                            // listed blocks staged in LDS at a time
 constexpr int kXcds = 8;                                   // accelerator dies, each with a private L2
 constexpr int kCohort = 64;                                // workgroups resident per XCD (32 CUs x 2)
 constexpr float kBigRowSum = 65536.0f;                     // lazy-reference overflow guard
@@ -72,44 +72,50 @@ __device__ inline TileBuffers tile_buffers(const bf16_t *Kh, const bf16_t *Vh, c
 // 16-lane groups of a ds_read_b128 hit 64 distinct banks, and -- unlike a swizzle -- the address of fragment k is
 // "lane base + k * 32 bytes", an immediate offset: one address register per tile instead of one per fragment.
 // LDS row r of the K' tile holds key (r & ~31) | swap23(r & 31).
-constexpr int kKRowB = 272, kVRowB = 144;                  // padded row sizes in bytes
-constexpr int kKTileB = KT * kKRowB;                       // 17408 = 17 KiB
-constexpr int kVTileB = 128 * kVRowB;                      // 18432 = 18 KiB
-constexpr int kKLoads = kKTileB / 1024, kVLoads = kVTileB / 1024;
+constexpr int kKRowB = 272;                                // padded K' row in bytes
+template <int KT>
+struct SubTile {
+    static constexpr int kVRowB = KT * 2 + 16;             // padded V'^T row: 144 (KT = 64) or 80 bytes (KT = 32)
+    static constexpr int kKLoads = (KT * kKRowB + 1023) / 1024;   // 1 KiB load chunks: 17 or 9 (the last half used)
+    static constexpr int kVLoads = 128 * kVRowB / 1024;    // 18 or 10
+    static constexpr int kKTileB = kKLoads * 1024, kVTileB = kVLoads * 1024;
+};
 
 // Per-lane global byte offsets of this wave's chunks inside a sub-tile, computed once.  One load instruction
 // moves 64 lanes x 16 bytes into 1 KiB of CONTIGUOUS LDS; the lane decides which global chunk lands there, so the
 // LDS image is the padded tile (lanes that fall on padding bytes fetch chunk 0 of their row, harmlessly).
-template <int WAVES>
+template <int WAVES, int KT>
 struct LaneOffsets {
-    uint32_t k[(kKLoads + WAVES - 1) / WAVES], v[(kVLoads + WAVES - 1) / WAVES];
+    uint32_t k[(SubTile<KT>::kKLoads + WAVES - 1) / WAVES], v[(SubTile<KT>::kVLoads + WAVES - 1) / WAVES];
 };
 
-template <int BLOCK, int WAVES>
-__device__ inline LaneOffsets<WAVES> lane_offsets(int wave, int lane)
+template <int BLOCK, int WAVES, int KT>
+__device__ inline LaneOffsets<WAVES, KT> lane_offsets(int wave, int lane)
 {
-    LaneOffsets<WAVES> o;
+    typedef SubTile<KT> ST;
+    LaneOffsets<WAVES, KT> o;
 #pragma unroll
-    for (int y = 0; y < (kKLoads + WAVES - 1) / WAVES; ++y) {
+    for (int y = 0; y < (ST::kKLoads + WAVES - 1) / WAVES; ++y) {
         const int pos = (wave + WAVES * y) * 1024 + lane * 16;
         const int r = pos / kKRowB, col = pos % kKRowB;
         const int key = (r & ~31) | swap23(r & 31);
-        o.k[y] = (uint32_t)(key * 256 + (col < 256 ? col : 0));
+        o.k[y] = r < KT ? (uint32_t)(key * 256 + (col < 256 ? col : 0)) : 0u;   // past the tile: padding of the chunk
     }
 #pragma unroll
-    for (int y = 0; y < (kVLoads + WAVES - 1) / WAVES; ++y) {
+    for (int y = 0; y < (ST::kVLoads + WAVES - 1) / WAVES; ++y) {
         const int pos = (wave + WAVES * y) * 1024 + lane * 16;
-        const int r = pos / kVRowB, col = pos % kVRowB;
-        // Vt: groups of 32 keys, each [128 features][32 keys]; the 64 keys of a sub-tile are two groups
-        o.v[y] = (uint32_t)(col < 128 ? ((col >> 6) * 128 + r) * 64 + (col & 63) : r * 64);
+        const int r = pos / ST::kVRowB, col = pos % ST::kVRowB;
+        // Vt: groups of 32 keys, each [128 features][32 keys]; a sub-tile is KT / 32 consecutive groups
+        o.v[y] = (uint32_t)(col < KT * 2 ? ((col >> 6) * 128 + r) * 64 + (col & 63) : r * 64);
     }
     return o;
 }
 
-template <int BLOCK, int WAVES>
+template <int BLOCK, int WAVES, int KT>
 __device__ inline void issue_subtile(unsigned char *kbuf, unsigned char *vbuf, int *kpos, const TileBuffers &buf,
-                                     const LaneOffsets<WAVES> &off, int j, int half, bool masked, int wave, int lane)
+                                     const LaneOffsets<WAVES, KT> &off, int j, int half, bool masked, int wave, int lane)
 {
+    constexpr int kKLoads = SubTile<KT>::kKLoads, kVLoads = SubTile<KT>::kVLoads;
     const int slot0 = j * BLOCK + half * KT;               // uniform
     // full rounds are unconditional; only the last, partial round of chunks tests the wave index
 #pragma unroll
@@ -122,7 +128,7 @@ __device__ inline void issue_subtile(unsigned char *kbuf, unsigned char *vbuf, i
         if (y < kVLoads / WAVES || wave < kVLoads % WAVES)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(buf.v, (lptr_t)(vbuf + (wave + WAVES * y) * 1024), 16, off.v[y],
                                                      j * (128 * BLOCK * 2) + half * (128 * KT * 2), 0, 0);
-    if (masked && wave == WAVES - 1)                       // original positions of the sub-tile's 64 keys
+    if (masked && wave == WAVES - 1)                       // original positions of 64 keys from the sub-tile's first on
         __builtin_amdgcn_raw_ptr_buffer_load_lds(buf.pos, (lptr_t)kpos, 4, lane * 4, slot0 * 4, 0, 0);
 }
 
@@ -160,11 +166,14 @@ __device__ inline bf16x8 exp2_pack8(const floatx16 &s, int base, float c2, float
 }
 
 // One sub-tile: S^T = K' Q'^T, softmax relative to the lane's reference, O^T += V'^T P^T.
-template <int BLOCK, int NT>
+template <int BLOCK, int NT, int KT>
 __device__ inline void compute_subtile(AttnState<NT> &st, const unsigned char *kbuf, const unsigned char *vbuf,
                                        const bf16x8 (&qf)[NT][8], const int (&qpos)[NT], const int *kpos, int room,
                                        bool masked, float c2, int ln, int lh)
 {
+    constexpr int MT = KT / 32;                                  // 32-key tiles per sub-tile
+    constexpr int KS = KT / 16;                                  // 16-key contraction steps per sub-tile
+    constexpr int kVRowB = SubTile<KT>::kVRowB;
     const unsigned char *kl = kbuf + ln * kKRowB + lh * 16;      // this lane's row / half inside a 32-key tile
     const unsigned char *vl = vbuf + ln * kVRowB + lh * 16;
     // S^T of one 32-key tile (8 MFMAs per query tile).  Operand fragments are fetched from LDS four at a time
@@ -191,7 +200,7 @@ __device__ inline void compute_subtile(AttnState<NT> &st, const unsigned char *k
     };
     // acc[nt][x] of tile mt: key (within the sub-tile) = 32 mt + 16 (x / 8) + 8 h + (x % 8), query = q0 + 32 nt + n
 
-    bf16x8 pf[NT][4];
+    bf16x8 pf[NT][KS];
     bool all_seen = true;
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) all_seen = all_seen && st.seen[nt];
@@ -202,7 +211,7 @@ __device__ inline void compute_subtile(AttnState<NT> &st, const unsigned char *k
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) rsum[nt] = 0.0f;
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt) {
+        for (int mt = 0; mt < MT; ++mt) {
             floatx16 acc[NT];
             s_tile(acc, mt);
 #pragma unroll
@@ -221,12 +230,12 @@ __device__ inline void compute_subtile(AttnState<NT> &st, const unsigned char *k
         }
     }
     if (exact) {
-        floatx16 acc_s[2][NT];
-        s_tile(acc_s[0], 0);
-        s_tile(acc_s[1], 1);
+        floatx16 acc_s[MT][NT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) s_tile(acc_s[mt], mt);
         if (masked) {
 #pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
+            for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
                 for (int u = 0; u < 2; ++u) {
                     const int k8 = 32 * mt + 16 * u + 8 * lh;  // 8 consecutive keys of this lane
@@ -245,7 +254,7 @@ __device__ inline void compute_subtile(AttnState<NT> &st, const unsigned char *k
         for (int nt = 0; nt < NT; ++nt) {
             float rmax = -INFINITY;
 #pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
+            for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
                 for (int x = 0; x < 16; ++x) rmax = fmaxf(rmax, acc_s[mt][nt][x]);
             rmax = fmaxf(rmax, __shfl_xor(rmax, 32, 64));
@@ -256,7 +265,7 @@ __device__ inline void compute_subtile(AttnState<NT> &st, const unsigned char *k
             const float alpha = was ? __builtin_amdgcn_exp2f(st.mref[nt] - mnew) : 1.0f;
             float rsum = 0.0f;
 #pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
+            for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
                 for (int u = 0; u < 2; ++u) pf[nt][2 * mt + u] = exp2_pack8(acc_s[mt][nt], 8 * u, c2, mnew, rsum);
             st.l[nt] = st.l[nt] * alpha + rsum;
@@ -272,21 +281,21 @@ __device__ inline void compute_subtile(AttnState<NT> &st, const unsigned char *k
     }
 
     {
-        bf16x8 fa[4], fb[4];
+        bf16x8 fa[KS], fb[KS];
 #pragma unroll
-        for (int x = 0; x < 4; ++x) fa[x] = *reinterpret_cast<const bf16x8 *>(vl + x * 32);
+        for (int x = 0; x < KS; ++x) fa[x] = *reinterpret_cast<const bf16x8 *>(vl + x * 32);
 #pragma unroll
-        for (int dt = 0; dt < 4; ++dt) {                   // one 32-row tile of O^T per step, 4 fragments each
-            bf16x8(&cur)[4] = (dt & 1) ? fb : fa;
-            bf16x8(&nxt)[4] = (dt & 1) ? fa : fb;
+        for (int dt = 0; dt < 4; ++dt) {                   // one 32-row tile of O^T per step, KS fragments each
+            bf16x8(&cur)[KS] = (dt & 1) ? fb : fa;
+            bf16x8(&nxt)[KS] = (dt & 1) ? fa : fb;
             __builtin_amdgcn_sched_barrier(0);
             if (dt < 3) {
 #pragma unroll
-                for (int x = 0; x < 4; ++x)
+                for (int x = 0; x < KS; ++x)
                     nxt[x] = *reinterpret_cast<const bf16x8 *>(vl + (dt + 1) * 32 * kVRowB + x * 32);
             }
 #pragma unroll
-            for (int k2 = 0; k2 < 4; ++k2)
+            for (int k2 = 0; k2 < KS; ++k2)
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt)
                     st.acc_o[dt][nt] =
@@ -296,8 +305,8 @@ __device__ inline void compute_subtile(AttnState<NT> &st, const unsigned char *k
     }
 }
 
-template <int BLOCK, int WAVES>
-__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVES / 2, WAVES / 2))) void attn_mfma_kernel(
+template <int BLOCK, int WAVES, int KT>
+__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_mfma_kernel(
     const bf16_t *__restrict__ Qp, const bf16_t *__restrict__ Kp, const bf16_t *__restrict__ Vt,
     const int32_t *__restrict__ qidx, const int32_t *__restrict__ kidx, const int32_t *__restrict__ row_cnt,
     const int32_t *__restrict__ col_idx, bf16_t *__restrict__ Op, float *__restrict__ lse,
@@ -308,9 +317,9 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
     constexpr int SUBS = BLOCK / KT;               // sub-tiles per key block
     static_assert(NT >= 1 && SUBS >= 1, "unsupported tiling");
 
-    __shared__ __align__(16) unsigned char kbuf0[kKTileB], kbuf1[kKTileB];   // 17 KiB each
-    __shared__ __align__(16) unsigned char vbuf0[kVTileB], vbuf1[kVTileB];   // 18 KiB each
-    __shared__ __align__(16) int kpos0[KT], kpos1[KT];
+    __shared__ __align__(16) unsigned char kbuf0[SubTile<KT>::kKTileB], kbuf1[SubTile<KT>::kKTileB];   // 17 / 9 KiB each
+    __shared__ __align__(16) unsigned char vbuf0[SubTile<KT>::kVTileB], vbuf1[SubTile<KT>::kVTileB];   // 18 / 10 KiB each
+    __shared__ __align__(16) int kpos0[64], kpos1[64];
     __shared__ int jl[kListChunk];                                            // validated block list, -1 = skip
 
     // Workgroup -> (query head, query block).  Workgroups are handed to the 8 XCDs round-robin by linear id and
@@ -365,7 +374,7 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
     const int32_t *cols = col_idx + ((size_t)bhq * g.T + i) * g.T;
     const TileBuffers buf = tile_buffers<BLOCK>(Kp + bhk * (size_t)g.n * D, Vt + bhk * (size_t)g.T * D * BLOCK,
                                                 kidx + bhk * (size_t)g.n, g.n, g.T);
-    const LaneOffsets<WAVES> off = lane_offsets<BLOCK, WAVES>(wave, lane);
+    const LaneOffsets<WAVES, KT> off = lane_offsets<BLOCK, WAVES, KT>(wave, lane);
 
     // The list is consumed in chunks staged in LDS (read back with LDS loads, which do not wait on the
     // asynchronous tile loads).  Entries outside the columns the causal mask admits become -1 and are skipped;
@@ -383,20 +392,20 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
         auto block_at = [&](int s) -> int { return __builtin_amdgcn_readfirstlane(jl[s / SUBS]); };
         {
             const int j0 = block_at(0);
-            if (j0 >= 0) issue_subtile<BLOCK, WAVES>(kbuf0, vbuf0, kpos0, buf, off, j0, 0, j0 >= jmask, wave, lane);
+            if (j0 >= 0) issue_subtile<BLOCK, WAVES, KT>(kbuf0, vbuf0, kpos0, buf, off, j0, 0, j0 >= jmask, wave, lane);
         }
         for (int s = 0; s < total; s += 2) {
             sync_tiles();                  // sub-tile s has landed in buffer 0; buffer 1 is free again
             if (s + 1 < total) {
                 const int j1 = block_at(s + 1);
                 if (j1 >= 0)
-                    issue_subtile<BLOCK, WAVES>(kbuf1, vbuf1, kpos1, buf, off, j1, (s + 1) % SUBS, j1 >= jmask, wave,
+                    issue_subtile<BLOCK, WAVES, KT>(kbuf1, vbuf1, kpos1, buf, off, j1, (s + 1) % SUBS, j1 >= jmask, wave,
                                                 lane);
             }
             {
                 const int j = block_at(s);
                 if (j >= 0)
-                    compute_subtile<BLOCK, NT>(st, kbuf0, vbuf0, qf, qpos, kpos0, g.n - j * BLOCK - (s % SUBS) * KT,
+                    compute_subtile<BLOCK, NT, KT>(st, kbuf0, vbuf0, qf, qpos, kpos0, g.n - j * BLOCK - (s % SUBS) * KT,
                                                j >= jmask, c2, ln, lh);
             }
             if (s + 1 >= total) break;
@@ -404,13 +413,13 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
             if (s + 2 < total) {
                 const int j2 = block_at(s + 2);
                 if (j2 >= 0)
-                    issue_subtile<BLOCK, WAVES>(kbuf0, vbuf0, kpos0, buf, off, j2, (s + 2) % SUBS, j2 >= jmask, wave,
+                    issue_subtile<BLOCK, WAVES, KT>(kbuf0, vbuf0, kpos0, buf, off, j2, (s + 2) % SUBS, j2 >= jmask, wave,
                                                 lane);
             }
             {
                 const int j = block_at(s + 1);
                 if (j >= 0)
-                    compute_subtile<BLOCK, NT>(st, kbuf1, vbuf1, qf, qpos, kpos1,
+                    compute_subtile<BLOCK, NT, KT>(st, kbuf1, vbuf1, qf, qpos, kpos1,
                                                g.n - j * BLOCK - ((s + 1) % SUBS) * KT, j >= jmask, c2, ln, lh);
             }
         }
@@ -586,11 +595,11 @@ extern "C" pbs_status pbs_attn_fwd(const pbs_problem *p, const void *Qp, const v
                 st = launch_attn_wide(g, Qp, Kp, Vt, qidx, kidx, row_cnt, col_idx, Op, lse, redo, s);
                 if (st != PBS_OK) return st;
             }
-            hipLaunchKernelGGL((attn_mfma_kernel<128, 4>), mgrid, dim3(256), 0, s, (const bf16_t *)Qp,
+            hipLaunchKernelGGL((attn_mfma_kernel<128, 4, 64>), mgrid, dim3(256), 0, s, (const bf16_t *)Qp,
                                (const bf16_t *)Kp, (const bf16_t *)Vt, qidx, kidx, row_cnt, col_idx, (bf16_t *)Op, lse,
                                (const int32_t *)redo, g);
         } else {
-            hipLaunchKernelGGL((attn_mfma_kernel<64, 2>), mgrid, dim3(128), 0, s, (const bf16_t *)Qp,
+            hipLaunchKernelGGL((attn_mfma_kernel<64, 2, 32>), mgrid, dim3(128), 0, s, (const bf16_t *)Qp,
                                (const bf16_t *)Kp, (const bf16_t *)Vt, qidx, kidx, row_cnt, col_idx, (bf16_t *)Op, lse,
                                (const int32_t *)nullptr, g);
         }
