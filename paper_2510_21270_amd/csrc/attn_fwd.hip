@@ -148,20 +148,30 @@ struct AttnState {
     bool seen[NT];          // the query has met at least one visible key, i.e. mref is meaningful
 };
 
-// p = exp2(s * c2 - shift) for 8 consecutive keys, packed to bf16; rsum += the rounded values
+// p = exp2(s * c2 - shift) for 8 consecutive keys, packed to bf16.  PLAIN_SUM = false: rsum += the rounded values,
+// one bf16 dot-product instruction per pair; true: rsum += the unrounded values, two additions per pair, which
+// overlap better with matrix instructions but need two more registers (the four-wave instantiation has none to spare).
+template <bool PLAIN_SUM>
 __device__ inline bf16x8 exp2_pack8(const floatx16 &s, int base, float c2, float shift, float &rsum)
 {
     const bf16x2 ones = {(bf16_t)1.0f, (bf16_t)1.0f};
     bf16x8 pk;
+    float odd = 0.0f;
 #pragma unroll
     for (int y = 0; y < 4; ++y) {
         floatx2 pr = {__builtin_amdgcn_exp2f(__builtin_fmaf(s[base + 2 * y], c2, -shift)),
                       __builtin_amdgcn_exp2f(__builtin_fmaf(s[base + 2 * y + 1], c2, -shift))};
         const bf16x2 t2 = __builtin_convertvector(pr, bf16x2);
-        rsum = __builtin_amdgcn_fdot2_f32_bf16(t2, ones, rsum, false);
+        if (PLAIN_SUM) {
+            rsum += pr[0];
+            odd += pr[1];
+        } else {
+            rsum = __builtin_amdgcn_fdot2_f32_bf16(t2, ones, rsum, false);
+        }
         pk[2 * y] = t2[0];
         pk[2 * y + 1] = t2[1];
     }
+    if (PLAIN_SUM) rsum += odd;
     return pk;
 }
 
@@ -217,7 +227,7 @@ __device__ inline void compute_subtile(AttnState<NT> &st, const unsigned char *k
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-                for (int u = 0; u < 2; ++u) pf[nt][2 * mt + u] = exp2_pack8(acc[nt], 8 * u, c2, st.mref[nt], rsum[nt]);
+                for (int u = 0; u < 2; ++u) pf[nt][2 * mt + u] = exp2_pack8<KT == 32>(acc[nt], 8 * u, c2, st.mref[nt], rsum[nt]);
         }
         bool big = false;
 #pragma unroll
@@ -267,7 +277,7 @@ __device__ inline void compute_subtile(AttnState<NT> &st, const unsigned char *k
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-                for (int u = 0; u < 2; ++u) pf[nt][2 * mt + u] = exp2_pack8(acc_s[mt][nt], 8 * u, c2, mnew, rsum);
+                for (int u = 0; u < 2; ++u) pf[nt][2 * mt + u] = exp2_pack8<KT == 32>(acc_s[mt][nt], 8 * u, c2, mnew, rsum);
             st.l[nt] = st.l[nt] * alpha + rsum;
             st.seen[nt] = now;
             st.mref[nt] = mnew;
