@@ -103,7 +103,6 @@ __global__ __launch_bounds__(64 * RB) void select_kernel(const double *__restric
     constexpr int THREADS = 64 * RB;
     extern __shared__ __align__(16) unsigned char smem_raw[];
     double *prob = reinterpret_cast<double *>(smem_raw);             // [RB][Tpad]
-    __shared__ __align__(16) double qs[128 * RB];                    // [e][RB]
 
     const int i = blockIdx.x;
     const int bhk = blockIdx.y / chunks, chunk = blockIdx.y % chunks;
@@ -113,14 +112,13 @@ __global__ __launch_bounds__(64 * RB) void select_kernel(const double *__restric
     const int ni = allowed_cols(i, g);
     const int tid = threadIdx.x;
 
-    for (int idx = tid; idx < g.d * RB; idx += THREADS) {
-        const int e = idx / RB, row = idx % RB;
-        qs[idx] = row < rows ? Qbar[((size_t)(bhq0 + row) * g.T + i) * g.d + e] : 0.0;
-    }
-    __syncthreads();
-
-    // logits, plain multiply-then-add in the order e = 0..d-1
+    // logits, plain multiply-then-add in the order e = 0..d-1.  The pooled queries of the RB rows are the same for
+    // every thread: read through wave-uniform addresses they arrive in scalar registers, no LDS involved.
     const double *kt = KbarT + (size_t)bhk * g.d * g.T;
+    const double *qrow[RB];
+#pragma unroll
+    for (int row = 0; row < RB; ++row)
+        qrow[row] = Qbar + ((size_t)(bhq0 + min(row, rows - 1)) * g.T + i) * g.d;   // surplus rows repeat the last one
     for (int j = tid; j < ni; j += THREADS) {
         double acc[RB];
 #pragma unroll
@@ -133,7 +131,7 @@ __global__ __launch_bounds__(64 * RB) void select_kernel(const double *__restric
             for (int u = 0; u < 8; ++u)
 #pragma unroll
                 for (int row = 0; row < RB; ++row)
-                    acc[row] = __dadd_rn(acc[row], __dmul_rn(qs[(e + u) * RB + row], kv[u]));
+                    acc[row] = __dadd_rn(acc[row], __dmul_rn(qrow[row][e + u], kv[u]));
         }
 #pragma unroll
         for (int row = 0; row < RB; ++row) prob[row * Tpad + j] = __dmul_rn(acc[row], (double)g.scale);
