@@ -2,11 +2,11 @@
 //
 // Everything that decides the discrete result runs in IEEE fp64 with the plain operation order (no fused
 // multiply-add in the logits), so the mask does not depend on how a machine rounds lower precision:
-//   1. pool_kernel     block means of Q' and K' (HBM-bound; sums of bf16 values are exact in fp64).
-//                      Kbar is stored d-major ([head][e][T]) so that the next kernel reads it coalesced.
-//   2. select_kernel   logits of up to four query heads of one group against the allowed columns, softmax,
-//                      the mass threshold by bisection (one wave per row), forced blocks, then bit-mask
-//                      words by wave ballot and the ascending column list by prefix popcount.
+//   1. pool_kernel     block means of K' (HBM-bound; sums of bf16 values are exact in fp64), stored d-major
+//                      ([head][e][T]) so that the next kernel reads them coalesced.
+//   2. select_kernel   block means of its own Q' blocks, then logits of up to four query heads of one group against
+//                      the allowed columns, softmax, the mass threshold by bisection (one wave per row), forced
+//                      blocks, then bit-mask words by wave ballot and the ascending column list by prefix popcount.
 #include "pbs_host.h"
 
 namespace pbs {
@@ -93,8 +93,8 @@ __device__ inline MassCount mass_at_least(const double *pr, int ni64, int lane, 
     return {wave_sum_dpp(acc), cnt};
 }
 
-template <int RB>
-__global__ __launch_bounds__(64 * RB) void select_kernel(const double *__restrict__ Qbar,    // [bhq][T][d]
+template <int RB, typename E>
+__global__ __launch_bounds__(64 * RB) void select_kernel(const E *__restrict__ Qp,           // [bhq][n][d]
                                                          const double *__restrict__ KbarT,   // [bhkv][d][T]
                                                          uint64_t *__restrict__ mask_bits,
                                                          int32_t *__restrict__ row_cnt,
@@ -103,6 +103,7 @@ __global__ __launch_bounds__(64 * RB) void select_kernel(const double *__restric
     constexpr int THREADS = 64 * RB;
     extern __shared__ __align__(16) unsigned char smem_raw[];
     double *prob = reinterpret_cast<double *>(smem_raw);             // [RB][Tpad]
+    __shared__ __align__(16) double qs[RB][128];                     // block means of the RB query rows (d <= 128)
 
     const int i = blockIdx.x;
     const int bhk = blockIdx.y / chunks, chunk = blockIdx.y % chunks;
@@ -112,13 +113,47 @@ __global__ __launch_bounds__(64 * RB) void select_kernel(const double *__restric
     const int ni = allowed_cols(i, g);
     const int tid = threadIdx.x;
 
-    // logits, plain multiply-then-add in the order e = 0..d-1.  The pooled queries of the RB rows are the same for
-    // every thread: read through wave-uniform addresses they arrive in scalar registers, no LDS involved.
-    const double *kt = KbarT + (size_t)bhk * g.d * g.T;
-    const double *qrow[RB];
+    // Block mean of query block i of row w, by wave w (sums of storage values in fp64; 16-byte column groups, four
+    // loads in flight per lane, then the row groups of the wave are added up).  Pooling Q' here instead of in a
+    // kernel of its own lets the 1 GiB read of Q' overlap with the arithmetic of other workgroups.
+    {
+        constexpr int VEC = 16 / sizeof(E);
+        typedef E vec_t __attribute__((ext_vector_type(VEC)));
+        const int w = tid >> 6, lane = tid & 63;
+        const int cpr = g.d / VEC;                                   // 8 .. 32 column groups
+        const int RG = 64 / cpr;                                     // row groups of a wave
+        const int cg = lane % cpr, rg = lane / cpr;
+        const int lo = i * g.block, hi = min(g.n, lo + g.block);
+        double acc[VEC];
 #pragma unroll
-    for (int row = 0; row < RB; ++row)
-        qrow[row] = Qbar + ((size_t)(bhq0 + min(row, rows - 1)) * g.T + i) * g.d;   // surplus rows repeat the last one
+        for (int u = 0; u < VEC; ++u) acc[u] = 0.0;
+        if (w < rows) {
+            const E *X = Qp + (size_t)(bhq0 + w) * g.n * g.d + cg * VEC;
+            for (int r0 = lo + rg; r0 < hi; r0 += 4 * RG) {
+                vec_t v[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    v[q] = vec_t{};
+                    if (r0 + q * RG < hi) v[q] = *reinterpret_cast<const vec_t *>(X + (size_t)(r0 + q * RG) * g.d);
+                }
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (r0 + q * RG < hi)
+#pragma unroll
+                        for (int u = 0; u < VEC; ++u) acc[u] += (double)ElemTraits<E>::to_float(v[q][u]);
+            }
+        }
+        for (int o = cpr; o < 64; o <<= 1)
+#pragma unroll
+            for (int u = 0; u < VEC; ++u) acc[u] += __shfl_xor(acc[u], o, 64);
+        if (rg == 0)
+#pragma unroll
+            for (int u = 0; u < VEC; ++u) qs[w][cg * VEC + u] = acc[u] / (double)(hi - lo);
+    }
+    __syncthreads();
+
+    // logits, plain multiply-then-add in the order e = 0..d-1
+    const double *kt = KbarT + (size_t)bhk * g.d * g.T;
     for (int j = tid; j < ni; j += THREADS) {
         double acc[RB];
 #pragma unroll
@@ -131,7 +166,7 @@ __global__ __launch_bounds__(64 * RB) void select_kernel(const double *__restric
             for (int u = 0; u < 8; ++u)
 #pragma unroll
                 for (int row = 0; row < RB; ++row)
-                    acc[row] = __dadd_rn(acc[row], __dmul_rn(qrow[row][e + u], kv[u]));
+                    acc[row] = __dadd_rn(acc[row], __dmul_rn(qs[row][e + u], kv[u]));
         }
 #pragma unroll
         for (int row = 0; row < RB; ++row) prob[row * Tpad + j] = __dmul_rn(acc[row], (double)g.scale);
@@ -231,8 +266,8 @@ __global__ __launch_bounds__(64 * RB) void select_kernel(const double *__restric
     if (lane == 0) row_cnt[orow] = base;
 }
 
-template <int RB>
-static pbs_status launch_select(const double *Qbar, const double *KbarT, uint64_t *mask_bits, int32_t *row_cnt,
+template <int RB, typename E>
+static pbs_status launch_select(const E *Qp, const double *KbarT, uint64_t *mask_bits, int32_t *row_cnt,
                                 int32_t *col_idx, const Geo &g, hipStream_t s)
 {
     const int chunks = (g.r + RB - 1) / RB;
@@ -241,14 +276,14 @@ static pbs_status launch_select(const double *Qbar, const double *KbarT, uint64_
     if (lds > 32 * 1024) {
         static bool attr_set = false;
         if (!attr_set) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void *>(&select_kernel<RB>),
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(&select_kernel<RB, E>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize,
                                     RB * kMaxT * (int)sizeof(double)) != hipSuccess)
                 return PBS_ERR_HIP;
             attr_set = true;
         }
     }
-    hipLaunchKernelGGL(select_kernel<RB>, dim3(g.T, g.batch * g.h_kv * chunks), dim3(64 * RB), lds, s, Qbar, KbarT,
+    hipLaunchKernelGGL((select_kernel<RB, E>), dim3(g.T, g.batch * g.h_kv * chunks), dim3(64 * RB), lds, s, Qp, KbarT,
                        mask_bits, row_cnt, col_idx, g, chunks, Tpad);
     return launch_status();
 }
@@ -256,8 +291,7 @@ static pbs_status launch_select(const double *Qbar, const double *KbarT, uint64_
 size_t ws_block_mask(const pbs_problem *p)
 {
     const Geo g = make_geo(p);
-    return align_up((size_t)g.batch * g.h_q * g.T * g.d * sizeof(double), kWsAlign) +
-           align_up((size_t)g.batch * g.h_kv * g.T * g.d * sizeof(double), kWsAlign);
+    return align_up((size_t)g.batch * g.h_kv * g.T * g.d * sizeof(double), kWsAlign);   // pooled K', fp64, d-major
 }
 
 }  // namespace pbs
@@ -274,23 +308,22 @@ extern "C" pbs_status pbs_block_mask(const pbs_problem *p, const void *Qp, const
     if ((st = check_ws(p, PBS_STAGE_BLOCK_MASK, ws, ws_bytes)) != PBS_OK) return st;
     const Geo g = make_geo(p);
     hipStream_t s = (hipStream_t)stream;
-    double *Qbar = reinterpret_cast<double *>(ws);
-    double *KbarT = reinterpret_cast<double *>(reinterpret_cast<char *>(ws) +
-                                               align_up((size_t)g.batch * g.h_q * g.T * g.d * sizeof(double), kWsAlign));
-    const int nq = g.batch * g.h_q, nk = g.batch * g.h_kv;
+    double *KbarT = reinterpret_cast<double *>(ws);
+    const int nk = g.batch * g.h_kv;
     if (p->dtype == PBS_BF16) {
-        hipLaunchKernelGGL((pool_kernel<bf16_t, false>), dim3(g.T, nq), dim3(256), 0, s, (const bf16_t *)Qp, Qbar, g.n,
-                           g.d, g.block, g.T);
         hipLaunchKernelGGL((pool_kernel<bf16_t, true>), dim3(g.T, nk), dim3(256), 0, s, (const bf16_t *)Kp, KbarT, g.n,
                            g.d, g.block, g.T);
-    } else {
-        hipLaunchKernelGGL((pool_kernel<float, false>), dim3(g.T, nq), dim3(256), 0, s, (const float *)Qp, Qbar, g.n,
-                           g.d, g.block, g.T);
-        hipLaunchKernelGGL((pool_kernel<float, true>), dim3(g.T, nk), dim3(256), 0, s, (const float *)Kp, KbarT, g.n,
-                           g.d, g.block, g.T);
+        if ((st = launch_status()) != PBS_OK) return st;
+        const bf16_t *Q = (const bf16_t *)Qp;
+        if (g.r >= 3) return launch_select<4>(Q, KbarT, mask_bits, row_cnt, col_idx, g, s);
+        if (g.r == 2) return launch_select<2>(Q, KbarT, mask_bits, row_cnt, col_idx, g, s);
+        return launch_select<1>(Q, KbarT, mask_bits, row_cnt, col_idx, g, s);
     }
+    hipLaunchKernelGGL((pool_kernel<float, true>), dim3(g.T, nk), dim3(256), 0, s, (const float *)Kp, KbarT, g.n, g.d,
+                       g.block, g.T);
     if ((st = launch_status()) != PBS_OK) return st;
-    if (g.r >= 3) return launch_select<4>(Qbar, KbarT, mask_bits, row_cnt, col_idx, g, s);
-    if (g.r == 2) return launch_select<2>(Qbar, KbarT, mask_bits, row_cnt, col_idx, g, s);
-    return launch_select<1>(Qbar, KbarT, mask_bits, row_cnt, col_idx, g, s);
+    const float *Q = (const float *)Qp;
+    if (g.r >= 3) return launch_select<4>(Q, KbarT, mask_bits, row_cnt, col_idx, g, s);
+    if (g.r == 2) return launch_select<2>(Q, KbarT, mask_bits, row_cnt, col_idx, g, s);
+    return launch_select<1>(Q, KbarT, mask_bits, row_cnt, col_idx, g, s);
 }

@@ -101,8 +101,8 @@ def test_workspace_and_vt_sizes(lib):
     p = _p()
     T = 1024
     assert b.vt_bytes(p) == 8 * T * 128 * 128 * 2 == 8 * 131072 * 128 * 2
-    # pooled means of Q' and K' in fp64
-    assert b.workspace_bytes(p, b.STAGE_BLOCK_MASK) >= (32 + 8) * T * 128 * 8
+    # pooled means of K' in fp64 (those of Q' never leave the selection kernel)
+    assert b.workspace_bytes(p, b.STAGE_BLOCK_MASK) == 8 * T * 128 * 8
     assert b.workspace_bytes(p, b.STAGE_KEY_SCORES) > 0
     # one redo flag per query block for the 64-queries-per-wave kernel (bf16, d = 128, block = 128), nothing otherwise
     assert b.workspace_bytes(p, b.STAGE_ATTN_FWD) == 32 * T * 4
