@@ -219,8 +219,9 @@ def _random_shape(seed, wide):
     h_q = h_kv * int(rng.choice([1, 2, 4]))
     tau = float(rng.choice([0.3, 0.6, 0.9, 0.99]))
     flags = int(rng.integers(0, 2))
+    batch = int(rng.choice([1, 2, 3]))
     return wl.planted("rnd%d" % seed, 500 + seed, h_q, h_kv, n, d, block, segment, tau, dtype, 4,
-                      rope_base=5e5 if seed % 2 else None, flags=flags)
+                      rope_base=5e5 if seed % 2 else None, flags=flags, batch=batch)
 
 
 @pytest.mark.parametrize("wide", [True, False])
@@ -232,8 +233,8 @@ def test_random_shapes_stage_by_stage(lib, oracle, seed, wide):
     qidx = wl.random_segment_perm(seed, w.batch * w.h_q, w.n, w.segment).reshape(w.batch, w.h_q, w.n) if sigma else None
     res = oracle.pipeline(w.Q, w.K, w.V, w.block, w.segment, w.tau, flags=w.flags, qidx=qidx)
     p = make_problem(w)
-    what = "%s n=%d hq=%d hkv=%d d=%d block=%d segment=%d tau=%g flags=%d sigma=%s" % (
-        w.dtype, w.n, w.h_q, w.h_kv, w.d, w.block, w.segment, w.tau, w.flags, sigma)
+    what = "%s batch=%d n=%d hq=%d hkv=%d d=%d block=%d segment=%d tau=%g flags=%d sigma=%s" % (
+        w.dtype, w.batch, w.n, w.h_q, w.h_kv, w.d, w.block, w.segment, w.tau, w.flags, sigma)
     s = pbs.key_scores(p, to_dev(w.Q, w.dtype), to_dev(w.K, w.dtype)).cpu().numpy().astype(np.float64)
     np.testing.assert_allclose(s, res["s"], rtol=2e-3 if (w.dtype == "bf16" and w.d == 128) else 1e-5, atol=1e-37,
                                err_msg=what)

@@ -185,3 +185,13 @@ def test_coverage_equals_brute_force_attention_mass(oracle):
     # listing everything captures all of it
     full = oracle.coverage(Q, Kp, None, kidx, rc_all, ci_all, block, segment)
     np.testing.assert_allclose(full, 1.0, rtol=0, atol=1e-12)
+
+
+def test_batch_items_are_independent_pipelines(oracle):
+    # a batch of two equals the two single-item runs side by side, stage by stage
+    w = wl.planted("batch2", 31, 4, 2, 300, 32, 32, 64, 0.8, "f32", 4, batch=2)
+    both = oracle.pipeline(w.Q, w.K, w.V, w.block, w.segment, w.tau, flags=w.flags)
+    for b in range(2):
+        one = oracle.pipeline(w.Q[b:b + 1], w.K[b:b + 1], w.V[b:b + 1], w.block, w.segment, w.tau, flags=w.flags)
+        for key in ("s", "kidx", "mask", "row_cnt", "Op", "lse", "O"):
+            np.testing.assert_array_equal(both[key][b:b + 1], one[key], err_msg=key)
