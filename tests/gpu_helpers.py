@@ -44,9 +44,9 @@ def mask_from_bits(bits, T):
     return m.reshape(words.shape[:-1] + (-1,))[..., :T]
 
 
-def make_problem(w, tau=None, flags=None, segment=None):
+def make_problem(w, tau=None, flags=None, segment=None, scale=0.0):
     return pbs.problem(w.batch, w.h_q, w.h_kv, w.n, w.d, w.block, segment or w.segment, w.dtype,
-                       tau=w.tau if tau is None else tau, scale=0.0, flags=w.flags if flags is None else flags)
+                       tau=w.tau if tau is None else tau, scale=scale, flags=w.flags if flags is None else flags)
 
 
 def check_close(got, want, dtype, what=""):

@@ -231,10 +231,11 @@ def test_random_shapes_stage_by_stage(lib, oracle, seed, wide):
     w = _random_shape(seed, wide)
     sigma = seed % 3 == 0
     qidx = wl.random_segment_perm(seed, w.batch * w.h_q, w.n, w.segment).reshape(w.batch, w.h_q, w.n) if sigma else None
-    res = oracle.pipeline(w.Q, w.K, w.V, w.block, w.segment, w.tau, flags=w.flags, qidx=qidx)
-    p = make_problem(w)
-    what = "%s batch=%d n=%d hq=%d hkv=%d d=%d block=%d segment=%d tau=%g flags=%d sigma=%s" % (
-        w.dtype, w.batch, w.n, w.h_q, w.h_kv, w.d, w.block, w.segment, w.tau, w.flags, sigma)
+    scale = [0.0, 0.05, 0.2][seed % 3]                  # 0 = the default 1 / sqrt(d)
+    res = oracle.pipeline(w.Q, w.K, w.V, w.block, w.segment, w.tau, scale=scale, flags=w.flags, qidx=qidx)
+    p = make_problem(w, scale=scale)
+    what = "%s batch=%d n=%d hq=%d hkv=%d d=%d block=%d segment=%d tau=%g flags=%d sigma=%s scale=%g" % (
+        w.dtype, w.batch, w.n, w.h_q, w.h_kv, w.d, w.block, w.segment, w.tau, w.flags, sigma, scale)
     s = pbs.key_scores(p, to_dev(w.Q, w.dtype), to_dev(w.K, w.dtype)).cpu().numpy().astype(np.float64)
     np.testing.assert_allclose(s, res["s"], rtol=2e-3 if (w.dtype == "bf16" and w.d == 128) else 1e-5, atol=1e-37,
                                err_msg=what)
