@@ -225,7 +225,7 @@ def _random_shape(seed, wide):
 
 
 @pytest.mark.parametrize("wide", [True, False])
-@pytest.mark.parametrize("seed", range(10))
+@pytest.mark.parametrize("seed", range(30))
 def test_random_shapes_stage_by_stage(lib, oracle, seed, wide):
     # every stage on the oracle's output of the stage before, for shapes no other test names
     w = _random_shape(seed, wide)
