@@ -55,7 +55,7 @@ def to_dev(x, dtype):
     return torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).cuda()
 
 
-def cpu_baseline(w, seconds_budget=25.0):
+def cpu_baseline(w, seconds_budget=20.0, visited=None):
     """The oracle's attention loop (Algorithm 1, fp64, plain C + OpenMP) on a sample of query blocks with every
     allowed block listed and the identity key order; reported in the metric's unit (TFLOP/s over visited blocks)."""
     import numpy as np
@@ -94,9 +94,26 @@ def cpu_baseline(w, seconds_budget=25.0):
         rows.append([0, int(rng.integers(0, w.h_q)), i])
         total += ni
     secs, blocks = run(rows)
-    return {"value": blocks * flop_per_block / secs / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
-            "sample": "%d query blocks (rows in the upper half, all allowed blocks listed, identity key order), "
-                      "%d blocks of %dx%dx%d, fp64, %.1f s wall" % (len(rows), blocks, w.block, w.block, w.d, secs)}
+    out = {"value": blocks * flop_per_block / secs / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+           "sample": "%d query blocks (rows in the upper half, all allowed blocks listed, identity key order), "
+                     "%d blocks of %dx%dx%d, fp64, %.1f s wall" % (len(rows), blocks, w.block, w.block, w.d, secs)}
+    if visited is not None:
+        # the other stages in full, and the attention loop scaled from the sample to the layer's visited blocks
+        stages = {}
+        t0 = time.perf_counter()
+        s = oracle.key_scores(w.Q, w.K, w.block)
+        stages["key_scores"] = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        kidx_o = oracle.segment_argsort(s.astype(np.float32), w.segment)
+        Kp = oracle.gather_rows(w.K, kidx_o)
+        oracle.gather_rows(w.V, kidx_o)
+        stages["segment_permute"] = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        oracle.block_mask(w.Q, Kp, w.block, w.segment, w.tau, flags=w.flags)
+        stages["block_mask"] = time.perf_counter() - t0
+        stages["attn_fwd_extrapolated"] = secs * visited / blocks
+        out["stages_s"] = stages
+    return out
 
 
 def main():
@@ -272,7 +289,7 @@ def main():
     if "mfma_alone_tflops" in extras:
         out["roofline"]["frac_of_mfma_alone_random_operands"] = attn_tflops / extras["mfma_alone_tflops"]["random_operands"]
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w)
+        out["cpu_baseline"] = cpu_baseline(w, visited=None if given else visited)
     print(json.dumps(out))
 
 
