@@ -156,7 +156,8 @@ def test_lists_agree_with_mask(oracle):
 def test_permutation_raises_block_sparsity_when_keys_are_heavy(oracle):
     # The paper's central claim (Section "Global-Importance-based Permutation", Figure 2): clustering the heavy-hitter
     # keys at the head of each segment lets Algorithm 2 reach the same mass with far fewer blocks.  The strengthened
-    # extra workload has keys that are heavy for every query; with the literal configs they are not.
+    # extra workload has keys that are heavy for every query; with the literal configs they are not
+    # (4u has a smaller norm than a Gaussian key, so its softmax mass against unrelated queries is below average).
     from paper_2510_21270_amd import workloads as wl
     w = wl.c3_strong(n=8192, h_q=8, h_kv=2)
     T = w.T
