@@ -19,7 +19,10 @@
 namespace pbs {
 
 constexpr int kQRows = 128;            // logit tile rows (>= B')
-constexpr int kKeysPerWg = 1024;       // keys per workgroup in the MFMA sweeps
+constexpr int kMaxKeysPerWg = 1024;    // keys per workgroup in the MFMA sweeps when there are enough keys
+constexpr int kMinKeysPerWg = 128;     // one 32-key tile per wave
+constexpr int kSweepWgs = 512;         // the sweeps shorten their key ranges until this many workgroups exist
+                                       // (every workgroup first copies the 64 KiB split Qhat: more of them costs again)
 constexpr float kLog2e = 1.4426950408889634f;
 
 // ------------------------------------------------------------------ MFMA path: prep
@@ -80,7 +83,7 @@ __device__ inline void load_kfrags(bf16x8 (&kf)[8], const bf16_t *Kh, int key0, 
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void scores_sweep1_kernel(
     const bf16_t *__restrict__ K,
                                                             const bf16_t *__restrict__ qsplit,
-                                                            float2 *__restrict__ partial, Geo g)
+                                                            float2 *__restrict__ partial, Geo g, int kpw)
 {
     __shared__ __align__(16) bf16_t qs[2 * kQRows * 128];   // 64 KiB
     __shared__ float2 red[4][kQRows];
@@ -96,10 +99,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     float m[4], l[4];
 #pragma unroll
     for (int nt = 0; nt < 4; ++nt) { m[nt] = -INFINITY; l[nt] = 0.0f; }
-    const int key_end = min(g.n, (wg + 1) * kKeysPerWg);
+    const int key_end = min(g.n, (wg + 1) * kpw);
     bf16x8 kf[8], kn[8];                                     // current fragments and the prefetched next tile
-    load_kfrags(kf, Kh, min(wg * kKeysPerWg + wave * 32, g.n - 1), g.n, lane);
-    for (int key0 = wg * kKeysPerWg + wave * 32; key0 < key_end; key0 += 4 * 32) {
+    load_kfrags(kf, Kh, min(wg * kpw + wave * 32, g.n - 1), g.n, lane);
+    for (int key0 = wg * kpw + wave * 32; key0 < key_end; key0 += 4 * 32) {
         load_kfrags(kn, Kh, key0 + 4 * 32 < key_end ? key0 + 4 * 32 : key0, g.n, lane);   // last tile: a cached re-read
 #pragma unroll
         for (int nt = 0; nt < 4; ++nt) {
@@ -184,7 +187,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const bf16_t *__restrict__ K,
                                                             const bf16_t *__restrict__ qsplit,
                                                             const float *__restrict__ cvec,
-                                                            float *__restrict__ scores, Geo g)
+                                                            float *__restrict__ scores, Geo g, int kpw)
 {
     __shared__ __align__(16) bf16_t qs[2 * kQRows * 128];
     const int bh = blockIdx.y;
@@ -204,10 +207,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             cinit[mt][i] = cvec[(size_t)bh * kQRows + 32 * mt + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3)];
     __syncthreads();
     const bf16_t *Kh = K + (size_t)bh * g.n * 128;
-    const int key_end = min(g.n, (wg + 1) * kKeysPerWg);
+    const int key_end = min(g.n, (wg + 1) * kpw);
     bf16x8 kf[8], kn[8];
-    load_kfrags(kf, Kh, min(wg * kKeysPerWg + wave * 32, g.n - 1), g.n, lane);
-    for (int key0 = wg * kKeysPerWg + wave * 32; key0 < key_end; key0 += 4 * 32) {
+    load_kfrags(kf, Kh, min(wg * kpw + wave * 32, g.n - 1), g.n, lane);
+    for (int key0 = wg * kpw + wave * 32; key0 < key_end; key0 += 4 * 32) {
         load_kfrags(kn, Kh, key0 + 4 * 32 < key_end ? key0 + 4 * 32 : key0, g.n, lane);   // last tile: a cached re-read
         float sum = 0.0f;
 #pragma unroll
@@ -337,13 +340,22 @@ static bool use_mfma(const pbs_problem *p) { return p->dtype == PBS_BF16 && p->d
 
 constexpr int kGenericKeysPerChunk = 4096;
 
+// Keys per workgroup of the MFMA sweeps: 1024 for long inputs; halved (down to one tile per wave) while the
+// grid would hold fewer than kSweepWgs workgroups, so that short inputs still spread over all compute units.
+static int sweep_keys_per_wg(const Geo &g)
+{
+    int kpw = kMaxKeysPerWg;
+    while (kpw > kMinKeysPerWg && (long long)ceil_div(g.n, kpw) * g.batch * g.h_kv < kSweepWgs) kpw >>= 1;
+    return kpw;
+}
+
 size_t ws_key_scores(const pbs_problem *p)
 {
     const Geo g = make_geo(p);
     const size_t nbh = (size_t)g.batch * g.h_kv;
     const int bl = g.block < g.n ? g.block : g.n;
     if (use_mfma(p)) {
-        const size_t nwg = ceil_div(g.n, kKeysPerWg);
+        const size_t nwg = ceil_div(g.n, sweep_keys_per_wg(g));
         return align_up(nbh * 2 * kQRows * 128 * sizeof(bf16_t), kWsAlign) +
                align_up(nbh * nwg * kQRows * sizeof(float2), kWsAlign) + align_up(nbh * kQRows * sizeof(float), kWsAlign);
     }
@@ -399,7 +411,8 @@ extern "C" pbs_status pbs_key_scores(const pbs_problem *p, const void *Q, const 
     }
     const int nbh = g.batch * g.h_kv;
     const int bl = g.block < g.n ? g.block : g.n;
-    const int nwg = ceil_div(g.n, kKeysPerWg);
+    const int kpw = sweep_keys_per_wg(g);
+    const int nwg = ceil_div(g.n, kpw);
     bf16_t *qsplit = reinterpret_cast<bf16_t *>(w);
     w += align_up((size_t)nbh * 2 * kQRows * 128 * sizeof(bf16_t), kWsAlign);
     float2 *partial = reinterpret_cast<float2 *>(w);
@@ -407,11 +420,11 @@ extern "C" pbs_status pbs_key_scores(const pbs_problem *p, const void *Q, const 
     float *cvec = reinterpret_cast<float *>(w);
     hipLaunchKernelGGL(qhat_split_kernel, dim3(kQRows / 8, nbh), dim3(256), 0, s, (const bf16_t *)Q, qsplit, g, bl);
     if ((st = launch_status()) != PBS_OK) return st;
-    hipLaunchKernelGGL(scores_sweep1_kernel, dim3(nwg, nbh), dim3(256), 0, s, (const bf16_t *)K, qsplit, partial, g);
+    hipLaunchKernelGGL(scores_sweep1_kernel, dim3(nwg, nbh), dim3(256), 0, s, (const bf16_t *)K, qsplit, partial, g, kpw);
     if ((st = launch_status()) != PBS_OK) return st;
     hipLaunchKernelGGL(scores_merge_kernel, dim3(nbh), dim3(1024), 0, s, partial, cvec, nwg, bl);
     if ((st = launch_status()) != PBS_OK) return st;
     hipLaunchKernelGGL(scores_sweep2_kernel, dim3(nwg, nbh), dim3(256), 0, s, (const bf16_t *)K, qsplit, cvec, scores,
-                       g);
+                       g, kpw);
     return launch_status();
 }

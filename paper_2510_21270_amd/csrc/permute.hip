@@ -9,11 +9,15 @@ namespace pbs {
 // One workgroup sorts one segment in LDS.  Key = (~orderable(score)) << 32 | position-in-segment, so an
 // ascending 64-bit bitonic sort yields descending score with ties in ascending position.  -0.0 is
 // folded onto +0.0 first so that the bit order agrees with the arithmetic order.
+// One thread per compare-exchange pair (two pairs when the padded segment has 4096 keys).  The 64 pairs of a
+// wave at strides up to 64 lie inside 128 consecutive keys that no other wave touches, so those stages (49 of
+// the 55 at 1024 keys) are ordered by the wave's own in-order LDS accesses and only the wider strides meet at
+// a workgroup barrier.
 // grid = (G + 1, batch*h_kv); workgroup G writes the identity for the unpermuted tail.
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void segment_argsort_kernel(const float *__restrict__ scores,
-                                                              int32_t *__restrict__ kidx, int n, int segment,
-                                                              int G, int p2)
+__global__ __launch_bounds__(1024) void segment_argsort_kernel(const float *__restrict__ scores,
+                                                               int32_t *__restrict__ kidx, int n, int segment,
+                                                               int G, int p2)
 {
     extern __shared__ uint64_t keys[];
     const int g = blockIdx.x;
@@ -45,8 +49,15 @@ __global__ __launch_bounds__(256) void segment_argsort_kernel(const float *__res
                 const uint64_t ka = keys[a], kb = keys[b];
                 if ((ka > kb) == asc) { keys[a] = kb; keys[b] = ka; }
             }
-            __syncthreads();
+            // strides up to 64 wrote only the wave's own keys, which are all that its next stage reads
+            if (j > 64) {
+                __syncthreads();
+            } else {
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+            }
         }
+        if (k > 64) __syncthreads();                         // the next k starts at stride k, across waves
     }
     for (int t = threadIdx.x; t < segment; t += blockDim.x)
         kidx[base + (size_t)g * segment + t] = g * segment + (int32_t)(keys[t] & 0xffffffffu);
@@ -226,7 +237,8 @@ extern "C" pbs_status pbs_segment_permute(const pbs_problem *p, const float *sco
     if (scores) {
         int p2 = 1;
         while (p2 < g.segment) p2 <<= 1;
-        hipLaunchKernelGGL(segment_argsort_kernel, dim3(g.G + 1, nbh), dim3(256), (size_t)p2 * sizeof(uint64_t), s,
+        const int threads = p2 / 2 < 64 ? 64 : (p2 / 2 > 1024 ? 1024 : p2 / 2);
+        hipLaunchKernelGGL(segment_argsort_kernel, dim3(g.G + 1, nbh), dim3(threads), (size_t)p2 * sizeof(uint64_t), s,
                            scores, kidx, g.n, g.segment, g.G, p2);
     } else {
         const size_t total = (size_t)nbh * g.n;
