@@ -250,6 +250,21 @@ def main():
             extras["attention_mass_covered"] = {"mean": float(cov.mean()), "min_row": float(cov.min()),
                                                 "rows_below_tau": float((cov < w.tau).float().mean())}
             del cov
+        if not given:
+            # full causal attention in token order through the same kernel (every block up to the diagonal listed):
+            # the dense pass that the paper's speed-ups are quoted against, on this GPU; overwrites K', V' and O'
+            pbs.segment_permute(p, None, K, V, pipe.kidx, pipe.Kp, pipe.Vt)
+            rc_dense = (torch.arange(w.T, device="cuda", dtype=torch.int32) + 1).view(1, 1, w.T) \
+                .expand(w.batch, w.h_q, w.T).contiguous()
+            ci_dense = torch.arange(w.T, device="cuda", dtype=torch.int32).view(1, 1, 1, w.T) \
+                .expand(w.batch, w.h_q, w.T, w.T).contiguous()
+            ms_dense = timed(lambda: pbs.attn_fwd(p, Q, pipe.Kp, pipe.Vt, None, pipe.kidx, rc_dense, ci_dense,
+                                                  pipe.Op, ws=pipe.ws4), reps=2)
+            dense_blocks = w.batch * w.h_q * w.T * (w.T + 1) // 2
+            extras["dense_causal_same_kernel"] = {
+                "ms": ms_dense, "tflops": dense_blocks * 4.0 * w.block * w.block * w.d / ms_dense / 1e9,
+                "layer_speedup_of_the_sparse_path": ms_dense / ms_per_step}
+            del rc_dense, ci_dense
         # what the matrix units sustain on their own, with operand bits that cost no / realistic switching power
         extras["mfma_alone_tflops"] = {"zero_operands": pbs.mfma_rate_probe(False),
                                        "random_operands": pbs.mfma_rate_probe(True)}
