@@ -133,6 +133,9 @@ def main():
     ap.add_argument("--coverage", action="store_true",
                     help="after the timed region, also report the true attention mass inside the selected blocks "
                          "(two more attention passes, one of them over every admitted block)")
+    ap.add_argument("--dense-baseline", action="store_true",
+                    help="after the timed region, also time plain causal attention in token order through the same "
+                         "kernel (three more attention passes) and report the sparse layer's speed-up over it")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="after the timed region, run one plain device copy of known size through pbs_unpermute, so "
                          "that a rocprofv3 --pmc run of this command shows what FETCH_SIZE / WRITE_SIZE read for it")
@@ -250,7 +253,7 @@ def main():
             extras["attention_mass_covered"] = {"mean": float(cov.mean()), "min_row": float(cov.min()),
                                                 "rows_below_tau": float((cov < w.tau).float().mean())}
             del cov
-        if not given:
+        if args.dense_baseline and not given:
             # full causal attention in token order through the same kernel (every block up to the diagonal listed):
             # the dense pass that the paper's speed-ups are quoted against, on this GPU; overwrites K', V' and O'
             pbs.segment_permute(p, None, K, V, pipe.kidx, pipe.Kp, pipe.Vt)
