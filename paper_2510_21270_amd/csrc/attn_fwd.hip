@@ -565,12 +565,11 @@ static pbs_status launch_vector(const Geo &g, const void *Qp, const void *Kp, co
                                 float *lse, hipStream_t s)
 {
     const size_t lds = (size_t)2 * g.block * D * sizeof(float) + (size_t)g.block * sizeof(int);
-    static bool attr_set = false;
-    if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_vector_kernel<E, D>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 2048) != hipSuccess)
-            return PBS_ERR_HIP;
-        attr_set = true;
+    static std::atomic<unsigned long long> lds_raised{0};
+    if (lds > 32 * 1024) {
+        const pbs_status st = raise_lds_limit(reinterpret_cast<const void *>(&attn_vector_kernel<E, D>),
+                                              160 * 1024 - 2048, lds_raised);
+        if (st != PBS_OK) return st;
     }
     hipLaunchKernelGGL((attn_vector_kernel<E, D>), dim3(g.T, g.batch * g.h_q), dim3(2 * g.block), lds, s,
                        (const E *)Qp, (const E *)Kp, (const E *)Vt, qidx, kidx, row_cnt, col_idx, (E *)Op, lse, g);

@@ -273,15 +273,11 @@ static pbs_status launch_select(const E *Qp, const double *KbarT, uint64_t *mask
     const int chunks = (g.r + RB - 1) / RB;
     const int Tpad = (g.T + 63) & ~63;
     const size_t lds = (size_t)RB * Tpad * sizeof(double);
+    static std::atomic<unsigned long long> lds_raised{0};
     if (lds > 32 * 1024) {
-        static bool attr_set = false;
-        if (!attr_set) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void *>(&select_kernel<RB, E>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    RB * kMaxT * (int)sizeof(double)) != hipSuccess)
-                return PBS_ERR_HIP;
-            attr_set = true;
-        }
+        const pbs_status st = raise_lds_limit(reinterpret_cast<const void *>(&select_kernel<RB, E>),
+                                              RB * kMaxT * (int)sizeof(double), lds_raised);
+        if (st != PBS_OK) return st;
     }
     hipLaunchKernelGGL((select_kernel<RB, E>), dim3(g.T, g.batch * g.h_kv * chunks), dim3(64 * RB), lds, s, Qp, KbarT,
                        mask_bits, row_cnt, col_idx, g, chunks, Tpad);

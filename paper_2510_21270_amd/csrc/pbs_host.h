@@ -2,6 +2,8 @@
 #pragma once
 #include <math.h>
 
+#include <atomic>
+
 #include "pbs_device.h"
 
 namespace pbs {
@@ -60,6 +62,19 @@ inline pbs_status check_ws(const pbs_problem *p, int stage, const void *ws, size
 inline pbs_status launch_status()
 {
     return hipGetLastError() == hipSuccess ? PBS_OK : PBS_ERR_HIP;
+}
+
+// Raises a kernel's dynamic LDS limit once per device (the attribute belongs to the current device's copy of the
+// kernel).  `done` is a bit per device ordinal, one such word per kernel; devices beyond 63 set it on every call.
+inline pbs_status raise_lds_limit(const void *kernel, int bytes, std::atomic<unsigned long long> &done)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return PBS_ERR_HIP;
+    const bool tracked = dev >= 0 && dev < 64;
+    if (tracked && ((done.load(std::memory_order_acquire) >> dev) & 1ull)) return PBS_OK;
+    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess) return PBS_ERR_HIP;
+    if (tracked) done.fetch_or(1ull << dev, std::memory_order_release);
+    return PBS_OK;
 }
 
 }  // namespace pbs
