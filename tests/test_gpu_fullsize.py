@@ -147,3 +147,39 @@ def test_maximum_length_dense_equals_causal_attention_on_sampled_blocks():
         ref = torch.softmax(L.masked_fill(pos_k > pos_q, float("-inf")), dim=1) @ v
         err = (O[0, h, i * B:(i + 1) * B].float() - ref).abs()
         assert float(err.max()) <= 2e-2 and float(err.mean()) <= 2e-3, (h, i, float(err.max()), float(err.mean()))
+
+
+def test_element_offsets_beyond_32_bits_reproduce_the_last_group_run_on_its_own():
+    # 40 query heads x 524288 rows x 128 columns = 2.7e9 elements per tensor: the last GQA group lies wholly beyond
+    # element offset 2^31 in Q and O and beyond 2^32 in the block lists.  Every (batch, kv head) group is an
+    # independent pipeline with a fixed order of operations, so the big run must reproduce, bit for bit, what the same
+    # group gives as a problem of its own (whose offsets are small).
+    _state.clear()
+    torch.cuda.empty_cache()
+    N, Hq, Hkv, d, B, S = 524288, 40, 10, 128, 128, 1024
+    gen = torch.Generator(device="cuda").manual_seed(23)
+    Q = torch.empty(1, Hq, N, d, device="cuda", dtype=torch.bfloat16)
+    for h in range(Hq):
+        Q[0, h] = torch.randn(N, d, device="cuda", generator=gen).to(torch.bfloat16)
+    K = torch.randn(1, Hkv, N, d, device="cuda", generator=gen).to(torch.bfloat16)
+    V = torch.randn(1, Hkv, N, d, device="cuda", generator=gen).to(torch.bfloat16)
+    assert Q.numel() > 2 ** 31
+    big = pbs.Pipeline(pbs.problem(1, Hq, Hkv, N, d, B, S, "bf16", tau=0.02))
+    O = big.run(Q, K, V)
+    torch.cuda.synchronize()
+    r = Hq // Hkv
+    small = pbs.Pipeline(pbs.problem(1, r, 1, N, d, B, S, "bf16", tau=0.02))
+    O1 = small.run(Q[:, Hq - r:].contiguous(), K[:, Hkv - 1:].contiguous(), V[:, Hkv - 1:].contiguous())
+    torch.cuda.synchronize()
+    assert torch.equal(big.scores[:, Hkv - 1:], small.scores)
+    assert torch.equal(big.kidx[:, Hkv - 1:], small.kidx)
+    assert torch.equal(big.Kp[:, Hkv - 1:], small.Kp)
+    assert torch.equal(big.Vt[:, Hkv - 1:], small.Vt)
+    assert torch.equal(big.mask_bits[:, Hq - r:], small.mask_bits)
+    assert torch.equal(big.row_cnt[:, Hq - r:], small.row_cnt)
+    T = N // B
+    listed = torch.arange(T, device="cuda").view(1, 1, 1, T) < small.row_cnt.unsqueeze(-1)
+    assert torch.equal(torch.where(listed, big.col_idx[:, Hq - r:], -1), torch.where(listed, small.col_idx, -1))
+    assert 0 < int(small.row_cnt.sum()) < r * T * (T + 1) // 8          # sparse, and not empty
+    assert torch.equal(O[:, Hq - r:], O1)
+    assert torch.isfinite(O[:, Hq - r:].float()).all()
