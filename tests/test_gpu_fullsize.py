@@ -149,26 +149,28 @@ def test_maximum_length_dense_equals_causal_attention_on_sampled_blocks():
         assert float(err.max()) <= 2e-2 and float(err.mean()) <= 2e-3, (h, i, float(err.max()), float(err.mean()))
 
 
-def test_element_offsets_beyond_32_bits_reproduce_the_last_group_run_on_its_own():
-    # 40 query heads x 524288 rows x 128 columns = 2.7e9 elements per tensor: the last GQA group lies wholly beyond
-    # element offset 2^31 in Q and O and beyond 2^32 in the block lists.  Every (batch, kv head) group is an
-    # independent pipeline with a fixed order of operations, so the big run must reproduce, bit for bit, what the same
-    # group gives as a problem of its own (whose offsets are small).
+@pytest.mark.parametrize("dtype,d,Hq,Hkv,tau", [("bf16", 128, 40, 10, 0.02), ("f32", 64, 66, 33, 0.0)])
+def test_element_offsets_beyond_32_bits_reproduce_the_last_group_run_on_its_own(dtype, d, Hq, Hkv, tau):
+    # 40 query heads x 524288 rows x 128 columns (66 x 524288 x 64 for the fp32 kernels) = 2.7e9 (2.2e9) elements per
+    # tensor: the last GQA group lies wholly beyond element offset 2^31 in Q and O and beyond 2^32 in the block lists.
+    # Every (batch, kv head) group is an independent pipeline with a fixed order of operations, so the big run must
+    # reproduce, bit for bit, what the same group gives as a problem of its own (whose offsets are small).
     _state.clear()
     torch.cuda.empty_cache()
-    N, Hq, Hkv, d, B, S = 524288, 40, 10, 128, 128, 1024
+    N, B, S = 524288, 128, 1024
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
     gen = torch.Generator(device="cuda").manual_seed(23)
-    Q = torch.empty(1, Hq, N, d, device="cuda", dtype=torch.bfloat16)
+    Q = torch.empty(1, Hq, N, d, device="cuda", dtype=tdt)
     for h in range(Hq):
-        Q[0, h] = torch.randn(N, d, device="cuda", generator=gen).to(torch.bfloat16)
-    K = torch.randn(1, Hkv, N, d, device="cuda", generator=gen).to(torch.bfloat16)
-    V = torch.randn(1, Hkv, N, d, device="cuda", generator=gen).to(torch.bfloat16)
+        Q[0, h] = torch.randn(N, d, device="cuda", generator=gen).to(tdt)
+    K = torch.randn(1, Hkv, N, d, device="cuda", generator=gen).to(tdt)
+    V = torch.randn(1, Hkv, N, d, device="cuda", generator=gen).to(tdt)
     assert Q.numel() > 2 ** 31
-    big = pbs.Pipeline(pbs.problem(1, Hq, Hkv, N, d, B, S, "bf16", tau=0.02))
+    big = pbs.Pipeline(pbs.problem(1, Hq, Hkv, N, d, B, S, dtype, tau=tau))
     O = big.run(Q, K, V)
     torch.cuda.synchronize()
     r = Hq // Hkv
-    small = pbs.Pipeline(pbs.problem(1, r, 1, N, d, B, S, "bf16", tau=0.02))
+    small = pbs.Pipeline(pbs.problem(1, r, 1, N, d, B, S, dtype, tau=tau))
     O1 = small.run(Q[:, Hq - r:].contiguous(), K[:, Hkv - 1:].contiguous(), V[:, Hkv - 1:].contiguous())
     torch.cuda.synchronize()
     assert torch.equal(big.scores[:, Hkv - 1:], small.scores)
@@ -183,3 +185,5 @@ def test_element_offsets_beyond_32_bits_reproduce_the_last_group_run_on_its_own(
     assert 0 < int(small.row_cnt.sum()) < r * T * (T + 1) // 8          # sparse, and not empty
     assert torch.equal(O[:, Hq - r:], O1)
     assert torch.isfinite(O[:, Hq - r:].float()).all()
+    del big, small, Q, K, V, O, O1
+    torch.cuda.empty_cache()
