@@ -216,23 +216,34 @@ __device__ __forceinline__ void s_mfma(floatx16 (&s)[2], const bf16x8 (&kf)[8], 
 // become -inf, i.e. probability 0), and for queries that meet their first visible key the reference, set to the row
 // maximum of this sub-tile.  A reference, once set, never moves (see the note on kBigRowSum), so O^T is never
 // rescaled and the softmax itself is the same code for every sub-tile.
-__device__ __forceinline__ void prepare_tile(State &st, int nt, floatx16 &s, const int *kpos, int room, bool masked,
-                                             int qpos, float c2, int lh)
+__device__ __forceinline__ void mask_tile(floatx16 (&s)[2], const int *kpos, int room, const int (&qpos)[2], int lh)
 {
-    if (masked) {
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const int k8 = 16 * u + 8 * lh;                    // 8 consecutive keys of this lane
-            // original positions of the keys; slots past the end of the sequence hold 0 and are masked by lim
-            const int4 a = *reinterpret_cast<const int4 *>(kpos + k8);
-            const int4 b = *reinterpret_cast<const int4 *>(kpos + k8 + 4);
-            const int kp[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+    for (int u = 0; u < 2; ++u) {
+        const int k8 = 16 * u + 8 * lh;                        // 8 consecutive keys of this lane
+        // original positions of the keys; slots past the end of the sequence hold 0 and are masked by lim
+        const int4 a = *reinterpret_cast<const int4 *>(kpos + k8);
+        const int4 b = *reinterpret_cast<const int4 *>(kpos + k8 + 4);
+        const int kp[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+        if (room >= KS) {                                      // every key of the sub-tile exists (all but a ragged tail)
+#pragma unroll
+            for (int x = 0; x < 8; ++x) {
+                if (kp[x] > qpos[0]) s[0][8 * u + x] = -INFINITY;
+                if (kp[x] > qpos[1]) s[1][8 * u + x] = -INFINITY;
+            }
+        } else {
             const int lim = room - k8;                         // keys x >= lim of this group do not exist
 #pragma unroll
-            for (int x = 0; x < 8; ++x)
-                if (kp[x] > qpos || x >= lim) s[8 * u + x] = -INFINITY;
+            for (int x = 0; x < 8; ++x) {
+                if (kp[x] > qpos[0] || x >= lim) s[0][8 * u + x] = -INFINITY;
+                if (kp[x] > qpos[1] || x >= lim) s[1][8 * u + x] = -INFINITY;
+            }
         }
     }
+}
+
+__device__ __forceinline__ void set_reference(State &st, int nt, const floatx16 &s, float c2)
+{
     if (!__all(st.seen[nt])) {
         float rmax = -INFINITY;
 #pragma unroll
@@ -261,8 +272,9 @@ __device__ __forceinline__ void step(State &st, floatx16 (&s_cur)[2], floatx16 (
     bf16x8 vf[8];
     if (masked || !__all(st.seen[0] && st.seen[1])) {
         asm volatile("" ::: "memory");                     // keeps this rare block out of the straight-line code
-        prepare_tile(st, 0, s_cur[0], sg_v.pos, room, masked, qpos[0], c2, lh);
-        prepare_tile(st, 1, s_cur[1], sg_v.pos, room, masked, qpos[1], c2, lh);
+        if (masked) mask_tile(s_cur, sg_v.pos, room, qpos, lh);
+        set_reference(st, 0, s_cur[0], c2);
+        set_reference(st, 1, s_cur[1], c2);
     }
     __builtin_amdgcn_sched_barrier(0);
     // Softmax of score pair q (query tile q / 8, scores 2 (q % 8) and + 1) in three stages, issued in consecutive
