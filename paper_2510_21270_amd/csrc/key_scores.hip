@@ -10,9 +10,8 @@
 //
 // bf16, d = 128: both sweeps form the 128 x keys logit tile on the matrix cores (32x32x16 bf16 MFMA, fp32
 // accumulator).  Qhat is an fp32 mean, not a bf16 value, so it is pre-multiplied by scale*log2(e) and split
-// into two bf16 terms hi + lo; each tile takes two MFMAs per fragment.  K fragments come straight from
-// global memory: the contraction index may be permuted freely, so lane half h contracts d in [64h, 64h+64)
-// and every lane reads one contiguous 128-byte half row.
+// into two bf16 terms hi + lo; each tile takes two MFMAs per fragment.  A wave keeps the fragments of its 32 rows
+// of Qhat in registers and the K tiles go through LDS, shared by the four waves of a workgroup.
 // Everything else (fp32 inputs, d = 64): fp64 vector arithmetic, one thread per key.
 #include "pbs_host.h"
 
@@ -20,14 +19,14 @@ namespace pbs {
 
 constexpr int kQRows = 128;            // logit tile rows (>= B')
 constexpr int kMaxKeysPerWg = 1024;    // keys per workgroup in the MFMA sweeps when there are enough keys
-constexpr int kMinKeysPerWg = 128;     // one 32-key tile per wave
+constexpr int kMinKeysPerWg = 256;     // shorter ranges do not pay for a workgroup's start (Qhat fragments, first tiles)
 constexpr int kSweepWgs = 512;         // the sweeps shorten their key ranges until this many workgroups exist
                                        // (every workgroup first copies the 64 KiB split Qhat: more of them costs again)
 constexpr float kLog2e = 1.4426950408889634f;
 
 // ------------------------------------------------------------------ MFMA path: prep
-// qsplit[bh][term][row][dswz]: row-major 128 x 128 bf16, 16-byte chunks XOR-swizzled by (row & 15) so that a
-// flat copy into LDS is bank-conflict free for the fragment reads.  Rows >= bl are zero.
+// qsplit[bh][term][row][dswz]: row-major 128 x 128 bf16, 16-byte chunks XOR-permuted by (row & 15) (the lanes of a
+// fragment load then spread over the 16 chunk positions of their rows).  Rows >= bl are zero.
 __global__ __launch_bounds__(256) void qhat_split_kernel(const bf16_t *__restrict__ Q, bf16_t *__restrict__ qsplit,
                                                          Geo g, int bl)
 {
@@ -60,98 +59,139 @@ __global__ __launch_bounds__(256) void qhat_split_kernel(const bf16_t *__restric
     *reinterpret_cast<bf16x4 *>(lo + dst) = vl;
 }
 
-// Fragment of the split Qhat held in LDS: rows 32*tile + (lane & 31), contraction chunk for k-step ks.
-__device__ inline bf16x8 qfrag(const bf16_t *lds, int tile, int ks, int lane)
+// ------------------------------------------------------------------ MFMA path: tiles and fragments
+// Wave w of a workgroup owns the logit rows 32 w .. 32 w + 31 and keeps their split Qhat fragments in registers
+// (8 k-steps x 2 terms x 4 registers); the K tiles of 32 keys go through LDS, where all four waves read them, so a
+// fragment read feeds two MFMAs and the tile is fetched from memory once.  A tile travels global -> registers ->
+// LDS; kTilesAhead tiles per workgroup are in flight in registers, and two LDS copies alternate so that one
+// barrier per tile suffices.
+constexpr int kTileKeys = 32;
+constexpr int kTilesAhead = 4;
+
+// 32 keys x 256 bytes; the 16-byte piece c of row r sits at r * 256 + ((c ^ (r & 15)) << 4): conflict-free for the
+// stores (16 lanes = the 16 pieces of a row) and for the fragment reads (16 lanes = 16 rows, one piece each).
+struct KTile {
+    unsigned char b[kTileKeys * 256];
+};
+
+// Thread tid moves pieces tid and tid + 256 of the 512 pieces of a tile (row = piece / 16, c = piece % 16).
+__device__ inline void ktile_fetch(uintx4 (&v)[2], const bf16_t *Kh, int key0, int n, int tid)
 {
-    const int row = tile * 32 + (lane & 31);
-    const int chunk = ((lane >> 5) * 8 + ks) ^ (row & 15);   // d = 64*h + 8*ks .. +8  -> chunk 8*h + ks
-    return *reinterpret_cast<const bf16x8 *>(lds + row * 128 + chunk * 8);
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        const int piece = tid + 256 * u;
+        int key = key0 + (piece >> 4);
+        if (key >= n) key = n - 1;                            // clamped; masked by the caller
+        v[u] = *reinterpret_cast<const uintx4 *>(Kh + (size_t)key * 128 + (piece & 15) * 8);
+    }
 }
 
-// K fragments of 32 keys starting at key0: lane (key = lane & 31, h = lane >> 5) reads d in [64h, 64h+64).
-__device__ inline void load_kfrags(bf16x8 (&kf)[8], const bf16_t *Kh, int key0, int n, int lane)
+__device__ inline void ktile_store(KTile &t, const uintx4 (&v)[2], int tid)
 {
-    int key = key0 + (lane & 31);
-    if (key >= n) key = n - 1;                                // clamped; masked by the caller
-    const bf16x8 *src = reinterpret_cast<const bf16x8 *>(Kh + (size_t)key * 128 + (lane >> 5) * 64);
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) kf[ks] = src[ks];
+    for (int u = 0; u < 2; ++u) {
+        const int piece = tid + 256 * u;
+        const int row = piece >> 4, c = piece & 15;
+        *reinterpret_cast<uintx4 *>(t.b + row * 256 + ((c ^ (row & 15)) << 4)) = v[u];
+    }
+}
+
+// MFMA operand of k-step ks: lane (key = lane & 31, h = lane >> 5) holds d = 16 ks + 8 h .. + 8 of its key.
+__device__ inline bf16x8 kfrag(const KTile &t, int ks, int lane)
+{
+    const int row = lane & 31, c = 2 * ks + (lane >> 5);
+    return *reinterpret_cast<const bf16x8 *>(t.b + row * 256 + ((c ^ (row & 15)) << 4));
+}
+
+// The wave's 32 rows of one term of the split Qhat, straight from qsplit (same d range per lane as kfrag).
+__device__ inline void load_qfrags(bf16x8 (&qf)[8], const bf16_t *term, int wave, int lane)
+{
+    const int row = wave * 32 + (lane & 31);
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+        const int c = 2 * ks + (lane >> 5);
+        qf[ks] = *reinterpret_cast<const bf16x8 *>(term + row * 128 + ((c ^ (row & 15)) << 3));
+    }
+}
+
+// Runs body(t, tile) for the tiles t = 0 .. ntiles - 1 of the keys from key_begin on, the tile being complete in
+// LDS.  The loops over the tiles in flight are fully unrolled, so their register copies have compile-time indices.
+template <typename Body>
+__device__ __forceinline__ void sweep_tiles(KTile (&kt)[2], const bf16_t *Kh, int key_begin, int ntiles, int n, int tid,
+                                            Body body)
+{
+    uintx4 pre[kTilesAhead][2];
+#pragma unroll
+    for (int a = 0; a < kTilesAhead; ++a) ktile_fetch(pre[a], Kh, min(key_begin + a * kTileKeys, n - 1), n, tid);
+    ktile_store(kt[0], pre[0], tid);
+    ktile_fetch(pre[0], Kh, min(key_begin + kTilesAhead * kTileKeys, n - 1), n, tid);
+    __syncthreads();
+    for (int t0 = 0; t0 < ntiles; t0 += kTilesAhead) {
+#pragma unroll
+        for (int a = 0; a < kTilesAhead; ++a) {
+            const int t = t0 + a;
+            if (t < ntiles) {                                  // uniform
+                // tile t + 1 leaves its registers for the LDS copy that tile t - 1 used, and its registers take
+                // tile t + 1 + kTilesAhead (reads past the range are clamped to the last key and never used)
+                ktile_store(kt[(a + 1) & 1], pre[(a + 1) % kTilesAhead], tid);
+                ktile_fetch(pre[(a + 1) % kTilesAhead], Kh, min(key_begin + (t + 1 + kTilesAhead) * kTileKeys, n - 1),
+                            n, tid);
+                body(t, kt[a & 1]);
+                __syncthreads();                               // tile t consumed, tile t + 1 visible
+            }
+        }
+    }
 }
 
 // ------------------------------------------------------------------ MFMA path: sweep 1
 // partial[bh][wg][row] = (max2, sumexp2) over the keys of workgroup wg, log2 domain.
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void scores_sweep1_kernel(
-    const bf16_t *__restrict__ K,
-                                                            const bf16_t *__restrict__ qsplit,
-                                                            float2 *__restrict__ partial, Geo g, int kpw)
+    const bf16_t *__restrict__ K, const bf16_t *__restrict__ qsplit, float2 *__restrict__ partial, Geo g, int kpw)
 {
-    __shared__ __align__(16) bf16_t qs[2 * kQRows * 128];   // 64 KiB
-    __shared__ float2 red[4][kQRows];
+    __shared__ __align__(16) KTile kt[2];
     const int bh = blockIdx.y, wg = blockIdx.x, nwg = gridDim.x;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    {
-        const uintx4 *src = reinterpret_cast<const uintx4 *>(qsplit + (size_t)bh * 2 * kQRows * 128);
-        uintx4 *dst = reinterpret_cast<uintx4 *>(qs);
-        for (int c = threadIdx.x; c < 2 * kQRows * 128 / 8; c += blockDim.x) dst[c] = src[c];
-    }
-    __syncthreads();
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    bf16x8 qh[8], ql[8];
+    load_qfrags(qh, qsplit + (size_t)bh * 2 * kQRows * 128, wave, lane);
+    load_qfrags(ql, qsplit + (size_t)bh * 2 * kQRows * 128 + kQRows * 128, wave, lane);
     const bf16_t *Kh = K + (size_t)bh * g.n * 128;
-    float m[4], l[4];
+    const int key_begin = wg * kpw, key_end = min(g.n, key_begin + kpw);
+    const int ntiles = ceil_div(key_end - key_begin, kTileKeys);
+    float m = -INFINITY, l = 0.0f;                           // row 32 wave + (lane & 31), this lane's half of the keys
+    sweep_tiles(kt, Kh, key_begin, ntiles, g.n, tid, [&](int t, const KTile &tile) {
+        floatx16 acc = {0};
 #pragma unroll
-    for (int nt = 0; nt < 4; ++nt) { m[nt] = -INFINITY; l[nt] = 0.0f; }
-    const int key_end = min(g.n, (wg + 1) * kpw);
-    bf16x8 kf[8], kn[8];                                     // current fragments and the prefetched next tile
-    load_kfrags(kf, Kh, min(wg * kpw + wave * 32, g.n - 1), g.n, lane);
-    for (int key0 = wg * kpw + wave * 32; key0 < key_end; key0 += 4 * 32) {
-        load_kfrags(kn, Kh, key0 + 4 * 32 < key_end ? key0 + 4 * 32 : key0, g.n, lane);   // last tile: a cached re-read
-#pragma unroll
-        for (int nt = 0; nt < 4; ++nt) {
-            asm volatile("" ::: "memory");                   // keeps the Qhat fragment reads inside the loop
-            floatx16 acc = {0};
-#pragma unroll
-            for (int ks = 0; ks < 8; ++ks) {
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qfrag(qs, nt, ks, lane), acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qfrag(qs + kQRows * 128, nt, ks, lane), acc, 0,
-                                                              0, 0);
-            }
-            // acc[i]: key = key0 + 8*(i/4) + 4*(lane>>5) + (i%4), query row = 32*nt + (lane & 31)
-            float tmax = -INFINITY;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int key = key0 + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
-                if (key >= g.n) acc[i] = -INFINITY;
-                tmax = fmaxf(tmax, acc[i]);
-            }
-            const float mn = fmaxf(m[nt], tmax);
-            if (mn != -INFINITY) {
-                float sum = 0.0f;
-#pragma unroll
-                for (int i = 0; i < 16; ++i) sum += exp2f(acc[i] - mn);
-                l[nt] = l[nt] * exp2f(m[nt] - mn) + sum;     // exp2f(-inf) = 0 on the first tile
-                m[nt] = mn;
-            }
+        for (int ks = 0; ks < 8; ++ks) {
+            const bf16x8 kf = kfrag(tile, ks, lane);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qh[ks], acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, ql[ks], acc, 0, 0, 0);
         }
+        // acc[i]: key = key0 + 8 (i / 4) + 4 (lane >> 5) + (i % 4), query row = 32 wave + (lane & 31)
+        const int key0 = key_begin + t * kTileKeys;
+        if (key0 + kTileKeys > g.n) {                          // the ragged last tile of the sequence
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) kf[ks] = kn[ks];
-    }
-    // merge the two lane halves, then the four waves
+            for (int i = 0; i < 16; ++i)
+                if (key0 + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3) >= g.n) acc[i] = -INFINITY;
+        }
+        float tmax = acc[0];
 #pragma unroll
-    for (int nt = 0; nt < 4; ++nt) {
-        const float mo = __shfl_xor(m[nt], 32, 64), lo = __shfl_xor(l[nt], 32, 64);
-        const float mn = fmaxf(m[nt], mo);
-        float ln = 0.0f;
-        if (mn != -INFINITY) ln = l[nt] * exp2f(m[nt] - mn) + lo * exp2f(mo - mn);
-        if (lane < 32) red[wave][nt * 32 + lane] = make_float2(mn, ln);
-    }
-    __syncthreads();
-    if (threadIdx.x < kQRows) {
-        float mn = -INFINITY;
-        for (int w = 0; w < 4; ++w) mn = fmaxf(mn, red[w][threadIdx.x].x);
-        float ln = 0.0f;
-        if (mn != -INFINITY)
-            for (int w = 0; w < 4; ++w) ln += red[w][threadIdx.x].y * exp2f(red[w][threadIdx.x].x - mn);
-        partial[((size_t)bh * nwg + wg) * kQRows + threadIdx.x] = make_float2(mn, ln);
-    }
+        for (int i = 1; i < 16; ++i) tmax = fmaxf(tmax, acc[i]);
+        const float mn = fmaxf(m, tmax);
+        if (mn != -INFINITY) {
+            // arguments are <= 0: the bare instruction (no denormal rescue) loses nothing that a sum near 1 would see
+            float sum = 0.0f;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) sum += __builtin_amdgcn_exp2f(acc[i] - mn);
+            l = l * __builtin_amdgcn_exp2f(m - mn) + sum;    // exp2(-inf) = 0 on the first tile
+            m = mn;
+        }
+    });
+    // merge the two lane halves; the rows of a wave are its own
+    const float mo = __shfl_xor(m, 32, 64), lo = __shfl_xor(l, 32, 64);
+    const float mn = fmaxf(m, mo);
+    float ln = 0.0f;
+    if (mn != -INFINITY) ln = l * exp2f(m - mn) + lo * exp2f(mo - mn);
+    if (lane < 32) partial[((size_t)bh * nwg + wg) * kQRows + wave * 32 + lane] = make_float2(mn, ln);
 }
 
 // c[bh][row] = -max - log2(bl * sumexp) for row < bl, -inf for the padding rows.
@@ -183,55 +223,45 @@ __global__ __launch_bounds__(1024) void scores_merge_kernel(const float2 *__rest
 }
 
 // ------------------------------------------------------------------ MFMA path: sweep 2
+// scores[key] = sum over the 128 rows of exp2(logit2 + c[row]): each wave sums its 32 rows per key into LDS, the
+// four partial sums of a key meet once at the end of the workgroup's range.
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void scores_sweep2_kernel(
-    const bf16_t *__restrict__ K,
-                                                            const bf16_t *__restrict__ qsplit,
-                                                            const float *__restrict__ cvec,
-                                                            float *__restrict__ scores, Geo g, int kpw)
+    const bf16_t *__restrict__ K, const bf16_t *__restrict__ qsplit, const float *__restrict__ cvec,
+    float *__restrict__ scores, Geo g, int kpw)
 {
-    __shared__ __align__(16) bf16_t qs[2 * kQRows * 128];
+    __shared__ __align__(16) KTile kt[2];
+    __shared__ float psum[4][kMaxKeysPerWg];
     const int bh = blockIdx.y;
     const int wg = gridDim.x - 1 - blockIdx.x;               // reverse order: reuse what sweep 1 left in cache
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    {
-        const uintx4 *src = reinterpret_cast<const uintx4 *>(qsplit + (size_t)bh * 2 * kQRows * 128);
-        uintx4 *dst = reinterpret_cast<uintx4 *>(qs);
-        for (int c = threadIdx.x; c < 2 * kQRows * 128 / 8; c += blockDim.x) dst[c] = src[c];
-    }
-    // the accumulator starts at c[row]; row = 32*mt + 8*(i/4) + 4*(lane>>5) + (i%4)
-    floatx16 cinit[4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    bf16x8 qh[8], ql[8];
+    load_qfrags(qh, qsplit + (size_t)bh * 2 * kQRows * 128, wave, lane);
+    load_qfrags(ql, qsplit + (size_t)bh * 2 * kQRows * 128 + kQRows * 128, wave, lane);
+    // the accumulator starts at c[row]; row = 32 wave + 8 (i / 4) + 4 (lane >> 5) + (i % 4)
+    floatx16 cinit;
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-        for (int i = 0; i < 16; ++i)
-            cinit[mt][i] = cvec[(size_t)bh * kQRows + 32 * mt + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3)];
-    __syncthreads();
+    for (int i = 0; i < 16; ++i)
+        cinit[i] = cvec[(size_t)bh * kQRows + 32 * wave + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3)];
     const bf16_t *Kh = K + (size_t)bh * g.n * 128;
-    const int key_end = min(g.n, (wg + 1) * kpw);
-    bf16x8 kf[8], kn[8];
-    load_kfrags(kf, Kh, min(wg * kpw + wave * 32, g.n - 1), g.n, lane);
-    for (int key0 = wg * kpw + wave * 32; key0 < key_end; key0 += 4 * 32) {
-        load_kfrags(kn, Kh, key0 + 4 * 32 < key_end ? key0 + 4 * 32 : key0, g.n, lane);   // last tile: a cached re-read
+    const int key_begin = wg * kpw, key_end = min(g.n, key_begin + kpw);
+    const int ntiles = ceil_div(key_end - key_begin, kTileKeys);
+    sweep_tiles(kt, Kh, key_begin, ntiles, g.n, tid, [&](int t, const KTile &tile) {
+        floatx16 acc = cinit;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            const bf16x8 kf = kfrag(tile, ks, lane);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qh[ks], kf, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ql[ks], kf, acc, 0, 0, 0);
+        }
         float sum = 0.0f;
 #pragma unroll
-        for (int mt = 0; mt < 4; ++mt) {
-            asm volatile("" ::: "memory");                   // keeps the Qhat fragment reads inside the loop
-            floatx16 acc = cinit[mt];
-#pragma unroll
-            for (int ks = 0; ks < 8; ++ks) {
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qfrag(qs, mt, ks, lane), kf[ks], acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qfrag(qs + kQRows * 128, mt, ks, lane), kf[ks], acc, 0,
-                                                              0, 0);
-            }
-#pragma unroll
-            for (int i = 0; i < 16; ++i) sum += exp2f(acc[i]);
-        }
+        for (int i = 0; i < 16; ++i) sum += __builtin_amdgcn_exp2f(acc[i]);
         sum += __shfl_xor(sum, 32, 64);
-        const int key = key0 + (lane & 31);
-        if (lane < 32 && key < g.n) scores[(size_t)bh * g.n + key] = sum;
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) kf[ks] = kn[ks];
-    }
+        if (lane < 32) psum[wave][t * kTileKeys + lane] = sum;      // key = key_begin + 32 t + lane
+    });
+    // the loop's last barrier has made every partial sum visible
+    for (int k = tid; k < key_end - key_begin; k += 256)
+        scores[(size_t)bh * g.n + key_begin + k] = (psum[0][k] + psum[1][k]) + (psum[2][k] + psum[3][k]);
 }
 
 // ------------------------------------------------------------------ generic path (fp64 accumulation)
