@@ -66,7 +66,7 @@ __global__ __launch_bounds__(256) void qhat_split_kernel(const bf16_t *__restric
 // LDS; kTilesAhead tiles per workgroup are in flight in registers, and two LDS copies alternate so that one
 // barrier per tile suffices.
 constexpr int kTileKeys = 32;
-constexpr int kTilesAhead = 4;
+constexpr int kTilesAhead = 2;
 
 // 32 keys x 256 bytes; the 16-byte piece c of row r sits at r * 256 + ((c ^ (r & 15)) << 4): conflict-free for the
 // stores (16 lanes = the 16 pieces of a row) and for the fragment reads (16 lanes = 16 rows, one piece each).
@@ -202,13 +202,20 @@ __global__ __launch_bounds__(1024) void scores_merge_kernel(const float2 *__rest
     __shared__ float2 red[8][kQRows];
     const int bh = blockIdx.x, row = threadIdx.x & (kQRows - 1), grp = threadIdx.x >> 7;
     float mn = -INFINITY, ln = 0.0f;
-    for (int w = grp; w < nwg; w += 8) {
-        const float2 pr = partial[((size_t)bh * nwg + w) * kQRows + row];
-        if (pr.x != -INFINITY) {
-            const float m2 = fmaxf(mn, pr.x);
-            ln = ln * exp2f(mn - m2) + pr.y * exp2f(pr.x - m2);
-            mn = m2;
+    for (int w0 = grp; w0 < nwg; w0 += 32) {                 // four independent loads per round trip
+        float2 pr[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int w = w0 + 8 * q;
+            pr[q] = w < nwg ? partial[((size_t)bh * nwg + w) * kQRows + row] : make_float2(-INFINITY, 0.0f);
         }
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            if (pr[q].x != -INFINITY) {
+                const float m2 = fmaxf(mn, pr[q].x);
+                ln = ln * exp2f(mn - m2) + pr[q].y * exp2f(pr[q].x - m2);
+                mn = m2;
+            }
     }
     red[grp][row] = make_float2(mn, ln);
     __syncthreads();
