@@ -51,7 +51,7 @@ __global__ __launch_bounds__(256) void pool_kernel(const E *__restrict__ X, doub
 #pragma unroll
     for (int u = 0; u < VEC; ++u) red[threadIdx.x * VEC + u] = acc[u];
     __syncthreads();
-    if (threadIdx.x < d) {
+    if ((int)threadIdx.x < d) {
         const int e = threadIdx.x, c = e / VEC, u = e % VEC;
         double s = 0.0;
         for (int q = 0; q < RG; ++q) s += red[(q * cpr + c) * VEC + u];

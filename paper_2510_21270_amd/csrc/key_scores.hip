@@ -363,7 +363,7 @@ __global__ __launch_bounds__(256) void scores_final_f64_kernel(const E *__restri
         __syncthreads();
         for (int idx = threadIdx.x; idx < nr * g.d; idx += blockDim.x)
             q[idx / g.d][idx % g.d] = qhat[((size_t)bh * bl + r0 + idx / g.d) * g.d + idx % g.d];
-        if (threadIdx.x < nr) st[threadIdx.x] = stats[(size_t)bh * bl + r0 + threadIdx.x];
+        if ((int)threadIdx.x < nr) st[threadIdx.x] = stats[(size_t)bh * bl + r0 + threadIdx.x];
         __syncthreads();
         for (int rr = 0; rr < nr; ++rr) {
             const double v = dot_f64(q[rr], krow, g.d) * (double)g.scale;
