@@ -253,3 +253,31 @@ def test_pipeline_replayed_from_a_hip_graph_matches_eager_runs():
         assert torch.equal(graphed.kidx, eager.kidx), it
         assert torch.equal(graphed.mask_bits, eager.mask_bits), it
         assert torch.equal(got, want), it
+
+
+def test_bench_prints_one_json_line_with_the_contract_fields():
+    # bench.py on its small functional workload, as the child process the driver would start
+    import json
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--workload", "small", "--steps", "2",
+                          "--warmup", "1"], capture_output=True, text=True, timeout=600, cwd=root)
+    assert res.returncode == 0, res.stderr[-2000:]
+    lines = [ln for ln in res.stdout.splitlines() if ln.strip()]
+    assert len(lines) == 1, res.stdout[-2000:]
+    out = json.loads(lines[0])
+    for key in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
+                "vs_baseline", "dtype", "data", "config", "roofline", "cpu_baseline"):
+        assert key in out, key
+    assert out["n_gpus"] == 1 and out["steps"] == 2 and out["warmup"] == 1 and out["data"] == "synthetic"
+    assert out["higher_is_better"] is True and out["vs_baseline"] is None and out["dtype"] == "bf16"
+    assert "workload" in out["config"] and "model" not in out["config"]
+    assert out["value"] > 0 and out["ms_per_step"] > 0
+    rf = out["roofline"]
+    assert rf["bound"] == "mfma" and rf["unit"] == "TFLOP/s" and rf["peak"] == 2500.0 and "traffic" in rf
+    assert abs(rf["frac"] - rf["achieved"] / rf["peak"]) < 1e-12 and 0 < rf["frac"] < 1
+    cb = out["cpu_baseline"]
+    assert cb["kind"] == "oracle" and cb["unit"] == out["unit"] and cb["cores"] >= 1 and cb["value"] > 0
+    assert isinstance(cb["sample"], str) and cb["sample"]
