@@ -133,6 +133,10 @@ def main():
     ap.add_argument("--coverage", action="store_true",
                     help="after the timed region, also report the true attention mass inside the selected blocks "
                          "(two more attention passes, one of them over every admitted block)")
+    ap.add_argument("--token-order-copy", action="store_true",
+                    help="set PBS_FLAG_TOKEN_ORDER_COPY: the permutation stage also writes K, V'^T and kidx in token "
+                         "order, and the attention evaluates every query block's own segment from that copy (blocks "
+                         "up to the diagonal, only the diagonal one under the causal test)")
     ap.add_argument("--dense-baseline", action="store_true",
                     help="after the timed region, also time plain causal attention in token order through the same "
                          "kernel (three more attention passes) and report the sparse layer's speed-up over it")
@@ -157,7 +161,8 @@ def main():
         w.K, w.V = np.repeat(w.K, r, axis=1), np.repeat(w.V, r, axis=1)
         w.extra = {k: v for k, v in w.extra.items() if k != "planted"}      # keyed by kv head
         w.h_kv, w.name = w.h_q, w.name + "_replicated_kv"
-    p = pbs.problem(w.batch, w.h_q, w.h_kv, w.n, w.d, w.block, w.segment, w.dtype, tau=w.tau, flags=w.flags)
+    flags = w.flags | (pbs.FLAG_TOKEN_ORDER_COPY if args.token_order_copy else 0)
+    p = pbs.problem(w.batch, w.h_q, w.h_kv, w.n, w.d, w.block, w.segment, w.dtype, tau=w.tau, flags=flags)
     Q, K, V = to_dev(w.Q, w.dtype), to_dev(w.K, w.dtype), to_dev(w.V, w.dtype)
     pipe = pbs.Pipeline(p)
     given = "row_cnt" in w.extra                      # config 5: caller-supplied block lists, identity key order
@@ -214,7 +219,7 @@ def main():
     # ---- untimed extras: where the planted keys end up, the inverse permutation with a real sigma, a plain copy
     extras = {}
     if not given and "planted" in w.extra:
-        kidx_h = pipe.kidx.cpu().numpy()
+        kidx_h = (pipe.kidx[0] if args.token_order_copy else pipe.kidx).cpu().numpy()
         seg = w.segment
         ranks = []
         for (b, h), pos in w.extra["planted"].items():
@@ -294,6 +299,7 @@ def main():
         "ms_per_layer": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
         "config": dict(w.describe(), visited_blocks=visited, causal_blocks=causal_total,
+                       own_segment_in_token_order=bool(args.token_order_copy),
                        density_vs_causal=visited / causal_total, given_mask=bool(given),
                        permuted=not (given or args.no_permute)),
         "stages_ms": stage_ms,

@@ -15,7 +15,7 @@ _lib = None
 
 PBS_F32, PBS_BF16 = 0, 1
 STAGE_KEY_SCORES, STAGE_SEGMENT_PERMUTE, STAGE_BLOCK_MASK, STAGE_ATTN_FWD, STAGE_UNPERMUTE = 1, 2, 3, 4, 5
-FLAG_FORCE_FIRST_BLOCK = 1
+FLAG_FORCE_FIRST_BLOCK, FLAG_TOKEN_ORDER_COPY = 1, 2
 
 EXPORTS = ["pbs_status_string", "pbs_validate", "pbs_workspace_bytes", "pbs_vt_bytes", "pbs_key_scores",
            "pbs_segment_permute", "pbs_permute_rows", "pbs_block_mask", "pbs_attn_fwd", "pbs_unpermute",
@@ -103,9 +103,26 @@ def alloc_workspace(p, stage, device="cuda"):
     return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)   # torch allocations are 512-B aligned
 
 
+def halves(p):
+    """1, or 2 when K', Vt and kidx carry a token-order copy behind the permuted tensor (PBS_FLAG_TOKEN_ORDER_COPY);
+    the copies are the leading axis of the tensors allocated here, so x[0] is what every other stage reads."""
+    return 2 if p.flags & FLAG_TOKEN_ORDER_COPY else 1
+
+
 def alloc_vt(p, device="cuda"):
     G = min(p.block, 32)                                   # keys per transposed group
-    return torch.empty((p.batch, p.h_kv, T_of(p), p.block // G, p.d, G), dtype=torch_dtype(p), device=device)
+    shape = (p.batch, p.h_kv, T_of(p), p.block // G, p.d, G)
+    return torch.empty((2,) + shape if halves(p) == 2 else shape, dtype=torch_dtype(p), device=device)
+
+
+def alloc_kp(p, device="cuda"):
+    shape = (p.batch, p.h_kv, p.n, p.d)
+    return torch.empty((2,) + shape if halves(p) == 2 else shape, dtype=torch_dtype(p), device=device)
+
+
+def alloc_kidx(p, device="cuda"):
+    shape = (p.batch, p.h_kv, p.n)
+    return torch.empty((2,) + shape if halves(p) == 2 else shape, dtype=torch.int32, device=device)
 
 
 def _ws_args(p, stage, ws):
@@ -126,10 +143,10 @@ def key_scores(p, Q, K, scores=None, ws=None):
 def segment_permute(p, scores, K, V, kidx=None, Kp=None, Vt=None, indices_only=False):
     dev = (K if K is not None else scores).device
     if kidx is None:
-        kidx = torch.empty((p.batch, p.h_kv, p.n), dtype=torch.int32, device=dev)
+        kidx = alloc_kidx(p, dev)
     if not indices_only:
         if Kp is None:
-            Kp = torch.empty_like(K)
+            Kp = alloc_kp(p, dev)
         if Vt is None:
             Vt = alloc_vt(p, dev)
     _check(load_library().pbs_segment_permute(ctypes.byref(p), _ptr(scores), _ptr(K), _ptr(V), _ptr(kidx), _ptr(Kp),
@@ -226,8 +243,8 @@ class Pipeline:
         self.p = p
         T, dt = T_of(p), torch_dtype(p)
         self.scores = torch.empty((p.batch, p.h_kv, p.n), dtype=torch.float32, device=device)
-        self.kidx = torch.empty((p.batch, p.h_kv, p.n), dtype=torch.int32, device=device)
-        self.Kp = torch.empty((p.batch, p.h_kv, p.n, p.d), dtype=dt, device=device)
+        self.kidx = alloc_kidx(p, device)
+        self.Kp = alloc_kp(p, device)
         self.Vt = alloc_vt(p, device)
         self.mask_bits = torch.empty((p.batch, p.h_q, T, (T + 63) // 64), dtype=torch.int64, device=device)
         self.row_cnt = torch.empty((p.batch, p.h_q, T), dtype=torch.int32, device=device)

@@ -557,7 +557,7 @@ size_t ws_attn_fwd(const pbs_problem *p)
 
 pbs_status launch_attn_wide(const Geo &g, const void *Qp, const void *Kp, const void *Vt, const int32_t *qidx,
                             const int32_t *kidx, const int32_t *row_cnt, const int32_t *col_idx, void *Op, float *lse,
-                            int32_t *redo, hipStream_t s);
+                            int32_t *redo, int tok_delta, hipStream_t s);
 
 template <typename E, int D>
 static pbs_status launch_vector(const Geo &g, const void *Qp, const void *Kp, const void *Vt, const int32_t *qidx,
@@ -601,7 +601,13 @@ extern "C" pbs_status pbs_attn_fwd(const pbs_problem *p, const void *Qp, const v
             // on ordinary inputs, then each workgroup of the second launch leaves at once) with the rescaling kernel
             int32_t *redo = narrow_only ? nullptr : reinterpret_cast<int32_t *>(ws);
             if (redo) {
-                st = launch_attn_wide(g, Qp, Kp, Vt, qidx, kidx, row_cnt, col_idx, Op, lse, redo, s);
+                // own segments from the token-order halves: identity sigma, whole blocks, and every byte of both
+                // halves of a head within reach of 32-bit buffer offsets
+                const long long rows = (long long)g.batch * g.h_kv * g.n;
+                const bool own_tok = (p->flags & PBS_FLAG_TOKEN_ORDER_COPY) && !qidx && g.n % 128 == 0 &&
+                                     (rows + g.n) * 256 < 0x7fffffffLL;
+                const int tok_delta = own_tok ? (int)(rows / 128) : 0;
+                st = launch_attn_wide(g, Qp, Kp, Vt, qidx, kidx, row_cnt, col_idx, Op, lse, redo, tok_delta, s);
                 if (st != PBS_OK) return st;
             }
             hipLaunchKernelGGL((attn_mfma_kernel<128, 4, 64>), mgrid, dim3(256), 0, s, (const bf16_t *)Qp,

@@ -419,11 +419,13 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     const bf16_t *__restrict__ Qp, const bf16_t *__restrict__ Kp, const bf16_t *__restrict__ Vt,
     const int32_t *__restrict__ qidx, const int32_t *__restrict__ kidx, const int32_t *__restrict__ row_cnt,
     const int32_t *__restrict__ col_idx, bf16_t *__restrict__ Op, float *__restrict__ lse,
-    int32_t *__restrict__ redo, Geo g)
+    int32_t *__restrict__ redo, Geo g, int tok_delta)
 {
     __shared__ Stage sg0, sg1, sg2, sg3;                   // 4 x 16 KiB
-    __shared__ int jl[kList];                              // listed blocks of the current chunk, -1 = not admissible
+    __shared__ int jl[kList];                              // current chunk of the list: block index to load
+    __shared__ int jm[kList];                              // ... keys of that block that exist, bit 30: token-level mask
     __shared__ int bad_any;
+    __shared__ int own_tail_ok;                            // the chunk ends with the whole own segment, ascending
 
     // Workgroup -> (query head, query block): cohorts of 64 rows of one kv head per XCD, longest lists first
     // (same decoding as the 32-queries-per-wave kernel).
@@ -474,28 +476,55 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     const int32_t *cols = col_idx + ((size_t)bhq * g.T + i) * g.T;
     constexpr int kRawDword = 0x00020000;                  // gfx9 descriptor word 3: raw 32-bit data format
     TileBuffers buf;
-    buf.k = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(Kp + bhk * (size_t)g.n * D), 0, g.n * 256, kRawDword);
+    // tok_delta > 0: a token-order copy of K', Vt and kidx lies tok_delta blocks (all batch * h_kv heads) behind the
+    // permuted one, so block j of this head in token order is block tok_delta + j of the same descriptors
+    const int reach = tok_delta * BLOCK + g.n;             // rows within reach of this head's descriptors
+    buf.k = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(Kp + bhk * (size_t)g.n * D), 0, reach * 256, kRawDword);
     buf.v = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(Vt + bhk * (size_t)g.T * D * BLOCK), 0,
-                                              g.T * D * BLOCK * 2, kRawDword);
-    buf.pos = __builtin_amdgcn_make_buffer_rsrc(const_cast<int32_t *>(kidx + bhk * (size_t)g.n), 0, g.n * 4, kRawDword);
+                                              (tok_delta + g.T) * (D * BLOCK * 2), kRawDword);
+    buf.pos = __builtin_amdgcn_make_buffer_rsrc(const_cast<int32_t *>(kidx + bhk * (size_t)g.n), 0, reach * 4, kRawDword);
     const LaneOffsets off = lane_offsets(wave, lane);
 
-    // An entry that the causal structure does not admit is staged as -1: it is loaded as block 0 and processed as a
-    // sub-tile with no existing key (room 0 on the exact path), which contributes nothing.
+    // The list is staged as (block to load, keys that exist | mask bit).  An entry that the causal structure does not
+    // admit is staged as block 0 with no existing key and the mask bit: a sub-tile that contributes nothing.
+    constexpr int kMaskBit = 1 << 30;
     auto entry = [&](int e) -> int { return __builtin_amdgcn_readfirstlane(jl[e]); };
+    auto entry_meta = [&](int e) -> int { return __builtin_amdgcn_readfirstlane(jm[e]); };
 
     for (int base = 0; base < cnt; base += kList) {
-        const int len = min(kList, cnt - base);
+        int len = min(kList, cnt - base);
         __syncthreads();                                   // previous chunk fully consumed
+        if (threadIdx.x == 0) own_tail_ok = 1;
         for (int t = threadIdx.x; t < len; t += 128) {
             const int j = cols[base + t];
-            jl[t] = (j >= 0 && j < ni) ? j : -1;
+            const bool ok = j >= 0 && j < ni;
+            jl[t] = ok ? j : 0;
+            jm[t] = ok ? (g.n - j * BLOCK) | (j >= jmask ? kMaskBit : 0) : kMaskBit;
         }
         __syncthreads();
+        // Own segment in token order: when the list ends with all blocks jmask .. ni - 1 of the query block's own
+        // (full) segment, ascending, they are replaced by the token-order blocks jmask .. i of the second halves.
+        // Keys of a segment are the same set in either order, so the visible keys are the same; in token order
+        // the blocks before the diagonal need no mask and those after it hold no visible key.
+        if (tok_delta > 0 && i / g.R < g.G && base + len == cnt && len >= ni - jmask) {
+            const int own = ni - jmask, first = len - own;
+            const int t = threadIdx.x;
+            if (t < own && (jl[first + t] != jmask + t || jm[first + t] != ((g.n - (jmask + t) * BLOCK) | kMaskBit)))
+                own_tail_ok = 0;
+            __syncthreads();
+            if (own_tail_ok) {
+                if (t <= i - jmask) {
+                    jl[first + t] = tok_delta + jmask + t;
+                    jm[first + t] = (g.n - (jmask + t) * BLOCK) | (jmask + t == i ? kMaskBit : 0);
+                }
+                len = first + i - jmask + 1;
+            }
+            __syncthreads();
+        }
 
         // prologue: the four parts of the first block, its first scores, the K' fragments of part 1
-        int jraw = entry(0);
-        int jc = jraw < 0 ? 0 : jraw;
+        int jc = entry(0);
+        int meta = entry_meta(0);
         issue_stage<0>(sg0, buf, off, jc, wave, lane);
         issue_stage<1>(sg1, buf, off, jc, wave, lane);
         issue_stage<2>(sg2, buf, off, jc, wave, lane);
@@ -516,10 +545,10 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 
         for (int e = 0; e < len; ++e) {
             const int enext = min(e + 1, len - 1);         // past the end: the last block again (results unused)
-            const int jnraw = entry(enext);
-            const int jn = jnraw < 0 ? 0 : jnraw;
-            const bool masked = jraw < 0 || jraw >= jmask;
-            const int room0 = jraw < 0 ? 0 : g.n - jraw * BLOCK;   // keys of the block that exist
+            const int jn = entry(enext);
+            const int meta_next = entry_meta(enext);
+            const bool masked = (meta & kMaskBit) != 0;
+            const int room0 = meta & (kMaskBit - 1);       // keys of the block that exist
             // part p: probabilities of part p; scores of part p + 1; O^T update with part p - 1; K' fragments of
             // part p + 2 (parts outside 0..3 are those of the neighbouring listed blocks).  Stage p is refilled with
             // K' part p of the next block and V'^T part p - 1 of the next block (part 3 of this block when p = 0).
@@ -528,8 +557,8 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
             step<1>(st, sb, sa, kf, qf, pb, pa, sg1, sg3, qpos, room0 - KS, masked, c2, lh, buf, off, jn, jn, wave, lane);
             step<2>(st, sa, sb, kf, qf, pa, pb, sg2, sg0, qpos, room0 - 2 * KS, masked, c2, lh, buf, off, jn, jn, wave, lane);
             step<3>(st, sb, sa, kf, qf, pb, pa, sg3, sg1, qpos, room0 - 3 * KS, masked, c2, lh, buf, off, jn, jn, wave, lane);
-            jraw = jnraw;
             jc = jn;
+            meta = meta_next;
         }
         drain(st, pa, sg0, off);
         __builtin_amdgcn_s_waitcnt(0x0F70);                // the loads issued past the end have landed too
@@ -571,12 +600,12 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 // redo: [batch * h_q * T] flags, written for every query block.
 pbs_status launch_attn_wide(const Geo &g, const void *Qp, const void *Kp, const void *Vt, const int32_t *qidx,
                             const int32_t *kidx, const int32_t *row_cnt, const int32_t *col_idx, void *Op, float *lse,
-                            int32_t *redo, hipStream_t s)
+                            int32_t *redo, int tok_delta, hipStream_t s)
 {
     const int ncoh = g.batch * g.h_kv * ((g.r * g.T + wide::kCohort - 1) / wide::kCohort);
     const dim3 grid((unsigned)(((ncoh + wide::kXcds - 1) / wide::kXcds) * wide::kCohort * wide::kXcds));
     hipLaunchKernelGGL(wide::attn_wide_kernel, grid, dim3(128), 0, s, (const bf16_t *)Qp, (const bf16_t *)Kp,
-                       (const bf16_t *)Vt, qidx, kidx, row_cnt, col_idx, (bf16_t *)Op, lse, redo, g);
+                       (const bf16_t *)Vt, qidx, kidx, row_cnt, col_idx, (bf16_t *)Op, lse, redo, g, tok_delta);
     return launch_status();
 }
 

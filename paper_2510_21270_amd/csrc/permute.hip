@@ -245,22 +245,36 @@ extern "C" pbs_status pbs_segment_permute(const pbs_problem *p, const float *sco
         hipLaunchKernelGGL(iota_kernel, dim3(grid_for(total, 256)), dim3(256), 0, s, kidx, g.n, total);
     }
     if ((st = launch_status()) != PBS_OK) return st;
+    const bool token_copy = (p->flags & PBS_FLAG_TOKEN_ORDER_COPY) != 0;
+    const size_t total = (size_t)nbh * g.n;
+    int32_t *kidx_tok = kidx + total;                      // second halves: token order
+    if (token_copy) {
+        hipLaunchKernelGGL(iota_kernel, dim3(grid_for(total, 256)), dim3(256), 0, s, kidx_tok, g.n, total);
+        if ((st = launch_status()) != PBS_OK) return st;
+    }
     if (!Kp) return PBS_OK;
     const size_t es = elem_size(p->dtype);
     const int cpr = (int)(g.d * es / 16);
-    hipLaunchKernelGGL(move_rows_kernel<false>, move_grid(g.n, cpr, nbh), dim3(256), 0, s,
-                       (const uintx4 *)K, (const int32_t *)kidx, (uintx4 *)Kp, g.n, ilog2(cpr));
-    if ((st = launch_status()) != PBS_OK) return st;
-    if (p->dtype == PBS_BF16) {
-        const size_t lds = (size_t)g.block * g.d * 2 + (size_t)(g.block / 8) * (64 / (vt_group(g.block) / 8)) * 4;   // tile + skew
-        hipLaunchKernelGGL(gather_vt_kernel<uint16_t>, dim3(g.T, nbh), dim3(256), lds, s, (const uint16_t *)V,
-                           (const int32_t *)kidx, (uint16_t *)Vt, g.n, g.d, g.block, g.T);
-    } else {
-        const size_t lds = (size_t)g.block * g.d * 4 + (size_t)(g.block / 4) * (64 / (vt_group(g.block) / 4)) * 4;
-        hipLaunchKernelGGL(gather_vt_kernel<uint32_t>, dim3(g.T, nbh), dim3(256), lds, s, (const uint32_t *)V,
-                           (const int32_t *)kidx, (uint32_t *)Vt, g.n, g.d, g.block, g.T);
+    const size_t vt_half = (size_t)nbh * g.T * g.d * g.block * es;
+    for (int half = 0; half < (token_copy ? 2 : 1); ++half) {
+        const int32_t *idx = half ? kidx_tok : kidx;
+        char *kdst = reinterpret_cast<char *>(Kp) + half * total * g.d * es;
+        char *vdst = reinterpret_cast<char *>(Vt) + half * vt_half;
+        hipLaunchKernelGGL(move_rows_kernel<false>, move_grid(g.n, cpr, nbh), dim3(256), 0, s, (const uintx4 *)K,
+                           half ? (const int32_t *)nullptr : idx, (uintx4 *)kdst, g.n, ilog2(cpr));
+        if ((st = launch_status()) != PBS_OK) return st;
+        if (p->dtype == PBS_BF16) {
+            const size_t lds = (size_t)g.block * g.d * 2 + (size_t)(g.block / 8) * (64 / (vt_group(g.block) / 8)) * 4;   // tile + skew
+            hipLaunchKernelGGL(gather_vt_kernel<uint16_t>, dim3(g.T, nbh), dim3(256), lds, s, (const uint16_t *)V, idx,
+                               (uint16_t *)vdst, g.n, g.d, g.block, g.T);
+        } else {
+            const size_t lds = (size_t)g.block * g.d * 4 + (size_t)(g.block / 4) * (64 / (vt_group(g.block) / 4)) * 4;
+            hipLaunchKernelGGL(gather_vt_kernel<uint32_t>, dim3(g.T, nbh), dim3(256), lds, s, (const uint32_t *)V, idx,
+                               (uint32_t *)vdst, g.n, g.d, g.block, g.T);
+        }
+        if ((st = launch_status()) != PBS_OK) return st;
     }
-    return launch_status();
+    return PBS_OK;
 }
 
 extern "C" pbs_status pbs_permute_rows(const pbs_problem *p, int32_t heads, const void *X, const int32_t *idx,

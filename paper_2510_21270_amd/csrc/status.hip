@@ -37,5 +37,6 @@ extern "C" size_t pbs_vt_bytes(const pbs_problem *p)
 {
     if (pbs::validate(p) != PBS_OK) return 0;
     const pbs::Geo g = pbs::make_geo(p);
-    return (size_t)g.batch * g.h_kv * g.T * g.d * g.block * pbs::elem_size(p->dtype);
+    const size_t half = (size_t)g.batch * g.h_kv * g.T * g.d * g.block * pbs::elem_size(p->dtype);
+    return (p->flags & PBS_FLAG_TOKEN_ORDER_COPY) ? 2 * half : half;
 }

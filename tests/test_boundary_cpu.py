@@ -111,6 +111,9 @@ def test_workspace_and_vt_sizes(lib):
     # partial last block is padded in Vt
     q = _p(n=1000, block=64, segment=256, d=64, dtype="f32", h_q=2, h_kv=2)
     assert b.vt_bytes(q) == 2 * 16 * 64 * 64 * 4
+    # a token-order copy behind the permuted tensor doubles it
+    p.flags = b.FLAG_TOKEN_ORDER_COPY
+    assert b.vt_bytes(p) == 2 * 8 * T * 128 * 128 * 2
 
 
 def test_paper_memory_figures():

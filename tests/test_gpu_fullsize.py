@@ -92,6 +92,22 @@ def test_full_size_attention_on_sampled_rows(oracle, name):
     vmax = st["V"].float().abs().amax(dim=2)                 # [1,Hkv,d]
     bound = vmax.repeat_interleave(w.h_q // w.h_kv, dim=1)[:, :, None, :] * 1.01 + 1e-3
     assert (Op.float().abs() <= bound).all()
+    # the same rows with every own segment taken from a token-order copy of K, V'^T and kidx behind the permuted ones
+    p2 = make_problem(w, flags=w.flags | pbs.FLAG_TOKEN_ORDER_COPY)
+    Kp2 = torch.stack([Kp_d, st["K"]])
+    Vt2 = torch.stack([Vt_d, to_dev(vt_layout(w.V, w.block), "bf16")])
+    del Kp_d, Vt_d
+    kidx2 = torch.stack([i32_dev(st["kidx"]), torch.arange(w.n, device="cuda", dtype=torch.int32)
+                         .expand(w.batch, w.h_kv, w.n)])
+    Op2, lse2 = pbs.attn_fwd(p2, st["Q"], Kp2, Vt2, None, kidx2, i32_dev(st["row_cnt"]), i32_dev(st["col_idx"]),
+                             torch.empty_like(Op), want_lse=True)
+    torch.cuda.synchronize()
+    for u, (b, h, i) in enumerate(rows):
+        sl = slice(i * w.block, (i + 1) * w.block)
+        check_close(to_host(Op2[b, h, sl]), want[u], "bf16", "%s row (%d,%d,%d), token-order copy" % (name, b, h, i))
+        np.testing.assert_allclose(lse2[b, h, sl].cpu().numpy(), want_lse[u], rtol=0, atol=2e-2)
+    assert not torch.equal(Op2, Op)                          # the copy was used
+    check_close(to_host(Op2[0, 0]), to_host(Op[0, 0]), "bf16", "%s head 0, copy against permuted order" % name)
 
 
 @pytest.mark.parametrize("rho", [0.10, 1.0])
@@ -149,8 +165,9 @@ def test_maximum_length_dense_equals_causal_attention_on_sampled_blocks():
         assert float(err.max()) <= 2e-2 and float(err.mean()) <= 2e-3, (h, i, float(err.max()), float(err.mean()))
 
 
-@pytest.mark.parametrize("dtype,d,Hq,Hkv,tau", [("bf16", 128, 40, 10, 0.02), ("f32", 64, 66, 33, 0.0)])
-def test_element_offsets_beyond_32_bits_reproduce_the_last_group_run_on_its_own(dtype, d, Hq, Hkv, tau):
+@pytest.mark.parametrize("dtype,d,Hq,Hkv,tau,flags", [("bf16", 128, 40, 10, 0.02, 0), ("f32", 64, 66, 33, 0.0, 0),
+                                                      ("bf16", 128, 40, 10, 0.02, pbs.FLAG_TOKEN_ORDER_COPY)])
+def test_element_offsets_beyond_32_bits_reproduce_the_last_group_run_on_its_own(dtype, d, Hq, Hkv, tau, flags):
     # 40 query heads x 524288 rows x 128 columns (66 x 524288 x 64 for the fp32 kernels) = 2.7e9 (2.2e9) elements per
     # tensor: the last GQA group lies wholly beyond element offset 2^31 in Q and O and beyond 2^32 in the block lists.
     # Every (batch, kv head) group is an independent pipeline with a fixed order of operations, so the big run must
@@ -166,17 +183,19 @@ def test_element_offsets_beyond_32_bits_reproduce_the_last_group_run_on_its_own(
     K = torch.randn(1, Hkv, N, d, device="cuda", generator=gen).to(tdt)
     V = torch.randn(1, Hkv, N, d, device="cuda", generator=gen).to(tdt)
     assert Q.numel() > 2 ** 31
-    big = pbs.Pipeline(pbs.problem(1, Hq, Hkv, N, d, B, S, dtype, tau=tau))
+    big = pbs.Pipeline(pbs.problem(1, Hq, Hkv, N, d, B, S, dtype, tau=tau, flags=flags))
     O = big.run(Q, K, V)
     torch.cuda.synchronize()
     r = Hq // Hkv
-    small = pbs.Pipeline(pbs.problem(1, r, 1, N, d, B, S, dtype, tau=tau))
+    small = pbs.Pipeline(pbs.problem(1, r, 1, N, d, B, S, dtype, tau=tau, flags=flags))
     O1 = small.run(Q[:, Hq - r:].contiguous(), K[:, Hkv - 1:].contiguous(), V[:, Hkv - 1:].contiguous())
     torch.cuda.synchronize()
     assert torch.equal(big.scores[:, Hkv - 1:], small.scores)
-    assert torch.equal(big.kidx[:, Hkv - 1:], small.kidx)
-    assert torch.equal(big.Kp[:, Hkv - 1:], small.Kp)
-    assert torch.equal(big.Vt[:, Hkv - 1:], small.Vt)
+    # with the token-order copy the tensors have a leading axis of two: permuted, token order (offsets up to 1.5e9
+    # bytes from a head's base inside the attention kernel)
+    assert torch.equal(big.kidx[..., Hkv - 1:, :], small.kidx)
+    assert torch.equal(big.Kp[..., Hkv - 1:, :, :], small.Kp)
+    assert torch.equal(big.Vt[..., Hkv - 1:, :, :, :, :], small.Vt)
     assert torch.equal(big.mask_bits[:, Hq - r:], small.mask_bits)
     assert torch.equal(big.row_cnt[:, Hq - r:], small.row_cnt)
     T = N // B

@@ -32,6 +32,8 @@ def _case(name):
         return wl.planted("bf16_d64", 14, 4, 4, 530, 64, 16, 128, 0.9, "bf16", 4)
     if name == "f32_b128":
         return wl.planted("f32_b128", 15, 2, 2, 700, 64, 128, 256, 0.9, "f32", 4)
+    if name == "bf16_even":                                                     # whole blocks: 5 segments + 3 tail blocks
+        return wl.planted("bf16_even", 17, 4, 2, 5 * 1024 + 384, 128, 128, 1024, 0.6, "bf16", 16, rope_base=5e5)
     if name == "bf16_r7":                                                       # Qwen-like GQA 7:1, bursts, ragged
         return wl.planted("bf16_r7", 16, 7, 1, 1536 + 19, 128, 128, 512, 0.95, "bf16", 8, rope_base=1e6, bursts=2,
                           burst_len=16)
@@ -255,3 +257,62 @@ def test_random_shapes_stage_by_stage(lib, oracle, seed, wide):
     check_close(to_host(O), res["O"], w.dtype, what + " O")
     np.testing.assert_allclose(lse.cpu().numpy(), res["lse"], rtol=0, atol=2e-2 if w.dtype == "bf16" else 1e-4,
                                err_msg=what)
+
+
+@pytest.mark.parametrize("name", ["bf16_even", "bf16_b128", "bf16_b64", "f32_d128"])
+def test_token_order_copy_of_the_own_segment(lib, oracle, name):
+    # PBS_FLAG_TOKEN_ORDER_COPY: the permutation stage writes K, V'^T and kidx a second time in token order, and the
+    # 64-queries-per-wave attention kernel takes a query block's own segment from that copy (whole blocks only:
+    # bf16_even; the other cases write the copy and must ignore it).  Same visible keys, so the oracle's O and
+    # lse must be met to the same tolerance; where the copy is ignored the output is bit-identical.
+    w, res = _oracle_run(oracle, name, False)
+    p0 = make_problem(w)
+    p1 = make_problem(w, flags=w.flags | pbs.FLAG_TOKEN_ORDER_COPY)
+    assert pbs.vt_bytes(p1) == 2 * pbs.vt_bytes(p0)
+    K, V = to_dev(w.K, w.dtype), to_dev(w.V, w.dtype)
+    scores = torch.from_numpy(res["s_handoff"]).cuda()
+    kidx, Kp, Vt = pbs.segment_permute(p1, scores, K, V)
+    torch.cuda.synchronize()
+    assert kidx.shape[0] == 2 and Kp.shape[0] == 2 and Vt.shape[0] == 2
+    np.testing.assert_array_equal(kidx[0].cpu().numpy(), res["kidx"])
+    np.testing.assert_array_equal(to_host(Kp[0]), res["Kp"].astype(np.float64))
+    np.testing.assert_array_equal(to_host(Vt[0]), vt_layout(res["Vp"], w.block).astype(np.float64))
+    assert torch.equal(kidx[1], torch.arange(w.n, device="cuda", dtype=torch.int32).expand(w.batch, w.h_kv, w.n))
+    assert torch.equal(Kp[1], K)
+    np.testing.assert_array_equal(to_host(Vt[1]), vt_layout(w.V, w.block).astype(np.float64))
+    kidx2, _, _ = pbs.segment_permute(p1, scores, None, None, indices_only=True)
+    assert torch.equal(kidx2, kidx)
+    # selection reads the first halves only
+    bits, cnt, cols = pbs.block_mask(p1, to_dev(res["Qp"], w.dtype), Kp)
+    np.testing.assert_array_equal(cnt.cpu().numpy(), res["row_cnt"])
+    # attention on the oracle's lists
+    Q = to_dev(res["Qp"], w.dtype)
+    rc, ci = i32_dev(res["row_cnt"]), i32_dev(res["col_idx"])
+    O1, lse1 = pbs.attn_fwd(p1, Q, Kp, Vt, None, kidx, rc, ci, want_lse=True)
+    O0, lse0 = pbs.attn_fwd(p0, Q, Kp[0], Vt[0], None, kidx[0], rc, ci, want_lse=True)
+    torch.cuda.synchronize()
+    check_close(to_host(O1), res["Op"], w.dtype, name + " O' with the token-order copy")
+    np.testing.assert_allclose(lse1.cpu().numpy(), res["lse"], rtol=0, atol=2e-2 if w.dtype == "bf16" else 1e-4)
+    if name == "bf16_even":
+        assert not torch.equal(O1, O0)                       # a different order of the sums: the copy was used
+        # lists in descending order do not end with the own segment: processed as listed, bit for bit
+        T = w.T
+        rev = ci.clone()
+        ar = torch.arange(T, device="cuda").view(1, 1, 1, T)
+        src = torch.clamp(rc.unsqueeze(-1).long() - 1 - ar, min=0)
+        rev = torch.where(ar < rc.unsqueeze(-1), torch.gather(ci, 3, src), ci)
+        R1 = pbs.attn_fwd(p1, Q, Kp, Vt, None, kidx, rc, rev)
+        R0 = pbs.attn_fwd(p0, Q, Kp[0], Vt[0], None, kidx[0], rc, rev)
+        assert torch.equal(R1, R0)
+        # a caller-supplied sigma switches the shortcut off as well
+        sig = i32_dev(wl.random_segment_perm(5, w.batch * w.h_q, w.n, w.segment).reshape(w.batch, w.h_q, w.n))
+        S1 = pbs.attn_fwd(p1, Q, Kp, Vt, sig, kidx, rc, ci)
+        S0 = pbs.attn_fwd(p0, Q, Kp[0], Vt[0], sig, kidx[0], rc, ci)
+        assert torch.equal(S1, S0)
+    else:
+        assert torch.equal(O1, O0) and torch.equal(lse1, lse0)
+    # the composed pipeline with the flag
+    pipe = pbs.Pipeline(p1)
+    O = pipe.run(to_dev(w.Q, w.dtype), K, V)
+    torch.cuda.synchronize()
+    assert torch.isfinite(O.float()).all()
