@@ -135,8 +135,9 @@ def main():
                          "(two more attention passes, one of them over every admitted block)")
     ap.add_argument("--token-order-copy", action="store_true",
                     help="set PBS_FLAG_TOKEN_ORDER_COPY: the permutation stage also writes K, V'^T and kidx in token "
-                         "order, and the attention evaluates every query block's own segment from that copy (blocks "
-                         "up to the diagonal, only the diagonal one under the causal test)")
+                         "order (twice the bytes of that stage), and the attention evaluates every query block's own "
+                         "segment from that copy: the blocks up to the diagonal, only the diagonal one under the causal "
+                         "test (the same visible keys as the R permuted blocks of the segment, so the same output)")
     ap.add_argument("--dense-baseline", action="store_true",
                     help="after the timed region, also time plain causal attention in token order through the same "
                          "kernel (three more attention passes) and report the sparse layer's speed-up over it")
@@ -161,11 +162,12 @@ def main():
         w.K, w.V = np.repeat(w.K, r, axis=1), np.repeat(w.V, r, axis=1)
         w.extra = {k: v for k, v in w.extra.items() if k != "planted"}      # keyed by kv head
         w.h_kv, w.name = w.h_q, w.name + "_replicated_kv"
-    flags = w.flags | (pbs.FLAG_TOKEN_ORDER_COPY if args.token_order_copy else 0)
+    given = "row_cnt" in w.extra                      # config 5: caller-supplied block lists, identity key order
+    token_copy = args.token_order_copy and not given
+    flags = w.flags | (pbs.FLAG_TOKEN_ORDER_COPY if token_copy else 0)
     p = pbs.problem(w.batch, w.h_q, w.h_kv, w.n, w.d, w.block, w.segment, w.dtype, tau=w.tau, flags=flags)
     Q, K, V = to_dev(w.Q, w.dtype), to_dev(w.K, w.dtype), to_dev(w.V, w.dtype)
     pipe = pbs.Pipeline(p)
-    given = "row_cnt" in w.extra                      # config 5: caller-supplied block lists, identity key order
     if given:
         row_cnt = torch.from_numpy(w.extra["row_cnt"]).cuda()
         col_idx = torch.from_numpy(w.extra["col_idx"]).cuda()
@@ -219,7 +221,7 @@ def main():
     # ---- untimed extras: where the planted keys end up, the inverse permutation with a real sigma, a plain copy
     extras = {}
     if not given and "planted" in w.extra:
-        kidx_h = (pipe.kidx[0] if args.token_order_copy else pipe.kidx).cpu().numpy()
+        kidx_h = (pipe.kidx[0] if token_copy else pipe.kidx).cpu().numpy()
         seg = w.segment
         ranks = []
         for (b, h), pos in w.extra["planted"].items():
@@ -278,10 +280,19 @@ def main():
                                        "random_operands": pbs.mfma_rate_probe(True)}
 
     cnt = (row_cnt if given else pipe.row_cnt).cpu().numpy().astype(np.int64)
-    visited = int(cnt.sum())
+    visited = int(cnt.sum())                           # blocks the masks list
     T = w.T
+    # blocks that are multiplied: with the token-order copy, a query block i of a full segment whose list ends with
+    # its R own-segment blocks inside one staged chunk of 256 entries takes i % R + 1 blocks for them instead of R
+    computed = visited
+    if (token_copy and w.dtype == "bf16" and w.d == 128 and w.block == 128 and w.n % 128 == 0 and
+            (w.batch * w.h_kv + 1) * w.n * 256 < 2 ** 31 - 1):
+        R, G = w.segment // w.block, w.n // w.segment
+        i = np.arange(T, dtype=np.int64)[None, None, :]
+        applies = (i // R < G) & (cnt >= R) & (((cnt - 1) % 256) + 1 >= R)
+        computed = int(visited - np.where(applies, R - (i % R + 1), 0).sum())
     causal_total = w.batch * w.h_q * T * (T + 1) // 2
-    flop = visited * 4.0 * w.block * w.block * w.d
+    flop = computed * 4.0 * w.block * w.block * w.d     # effective TFLOP/s counts computed blocks only
     es = 2 if w.dtype == "bf16" else 4
     kv_bytes = 2 * w.batch * w.h_kv * w.n * w.d * es
     q_bytes = w.batch * w.h_q * w.n * w.d * es
@@ -299,7 +310,7 @@ def main():
         "ms_per_layer": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
         "config": dict(w.describe(), visited_blocks=visited, causal_blocks=causal_total,
-                       own_segment_in_token_order=bool(args.token_order_copy),
+                       own_segment_in_token_order=bool(token_copy), computed_blocks=computed,
                        density_vs_causal=visited / causal_total, given_mask=bool(given),
                        permuted=not (given or args.no_permute)),
         "stages_ms": stage_ms,
