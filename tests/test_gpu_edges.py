@@ -184,6 +184,19 @@ def test_scores_climbing_far_above_the_first_keys_take_the_second_pass(oracle):
     want, want_lse = oracle.attn_fwd(Q, K, V, None, kidx, row_cnt, col_idx, block, want_lse=True)
     check_close(to_host(got), want, "bf16", "second pass")
     np.testing.assert_allclose(lse.cpu().numpy(), want_lse, atol=2e-2, rtol=2e-4)
+    # the same with segments of four blocks, every admitted block listed and the own segment taken from a token-order
+    # copy: the first pass flags the blocks all the same, and the second pass recomputes them from the lists as given
+    R = 4
+    p4 = pbs.problem(1, Hq, Hkv, n, d, block, R * block, "bf16", flags=pbs.FLAG_TOKEN_ORDER_COPY)
+    row_cnt4 = np.tile(((np.arange(T) // R + 1) * R).astype(np.int32), (1, Hq, 1))
+    Kd, Vd, kd = to_dev(K, "bf16"), to_dev(vt_layout(V, block), "bf16"), i32_dev(kidx)
+    ws.zero_()
+    got4, lse4 = pbs.attn_fwd(p4, to_dev(Q, "bf16"), torch.stack([Kd, Kd]), torch.stack([Vd, Vd]), None,
+                              torch.stack([kd, kd]), i32_dev(row_cnt4), i32_dev(col_idx), want_lse=True, ws=ws)
+    torch.cuda.synchronize()
+    assert ws[:Hq * T * 4].view(torch.int32).sum().item() >= Hq * (T - 3)
+    check_close(to_host(got4), want, "bf16", "second pass after a first pass on the token-order copy")
+    np.testing.assert_allclose(lse4.cpu().numpy(), want_lse, atol=2e-2, rtol=2e-4)
 
 
 def test_rescaling_kernel_alone_serves_block_128(oracle):
