@@ -316,3 +316,30 @@ def test_token_order_copy_of_the_own_segment(lib, oracle, name):
     O = pipe.run(to_dev(w.Q, w.dtype), K, V)
     torch.cuda.synchronize()
     assert torch.isfinite(O.float()).all()
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_token_order_copy_on_random_whole_block_shapes(lib, oracle, seed):
+    # seeded shapes made of whole blocks (so that the copy is used): segments of 1 to 8 blocks, with and without an
+    # unpermuted tail, batches of one or two, GQA groups of 1, 2 or 4
+    rng = np.random.default_rng(3000 + seed)
+    segment = int(rng.choice([128, 256, 512, 1024]))
+    n = 128 * int(rng.integers(1, 25))
+    h_kv = int(rng.choice([1, 2, 3]))
+    h_q = h_kv * int(rng.choice([1, 2, 4]))
+    tau = float(rng.choice([0.3, 0.6, 0.9]))
+    w = wl.planted("tok%d" % seed, 700 + seed, h_q, h_kv, n, 128, 128, segment, tau, "bf16", 4,
+                   rope_base=5e5 if seed % 2 else None, flags=int(rng.integers(0, 2)), batch=int(rng.choice([1, 2])))
+    res = oracle.pipeline(w.Q, w.K, w.V, w.block, w.segment, w.tau, flags=w.flags)
+    p = make_problem(w, flags=w.flags | pbs.FLAG_TOKEN_ORDER_COPY)
+    what = "batch=%d n=%d hq=%d hkv=%d segment=%d tau=%g flags=%d" % (w.batch, n, h_q, h_kv, segment, tau, w.flags)
+    kidx, Kp, Vt = pbs.segment_permute(p, torch.from_numpy(res["s_handoff"]).cuda(), to_dev(w.K, "bf16"),
+                                       to_dev(w.V, "bf16"))
+    np.testing.assert_array_equal(kidx[0].cpu().numpy(), res["kidx"], err_msg=what)
+    bits, cnt, cols = pbs.block_mask(p, to_dev(res["Qp"], "bf16"), Kp)
+    np.testing.assert_array_equal(mask_from_bits(bits, w.T), res["mask"], err_msg=what)
+    np.testing.assert_array_equal(cnt.cpu().numpy(), res["row_cnt"], err_msg=what)
+    Op, lse = pbs.attn_fwd(p, to_dev(res["Qp"], "bf16"), Kp, Vt, None, kidx, cnt, cols, want_lse=True)
+    torch.cuda.synchronize()
+    check_close(to_host(Op), res["Op"], "bf16", what + " O'")
+    np.testing.assert_allclose(lse.cpu().numpy(), res["lse"], rtol=0, atol=2e-2, err_msg=what)
