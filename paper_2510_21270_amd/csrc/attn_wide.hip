@@ -22,6 +22,10 @@
 // V'^T part (p + 3) % 4 of their blocks, which is what iteration t = p (mod 4) frees and refills.
 // A sub-tile that is not plain (token-level mask, queries without a visible key so far) first rewrites its scores
 // and references in a separate block, then goes through the same code.
+// The block list of a query block is staged in LDS in chunks, each entry as (block to load, keys that exist, mask
+// bit).  When K', Vt and kidx carry a token-order copy behind the permuted tensors (tok_delta > 0), the R own-segment
+// blocks at the end of a list are replaced, while staged, by the token-order blocks up to the diagonal; the loop
+// itself does not know the difference (a token-order block is just a block index beyond the permuted ones).
 #include "pbs_host.h"
 
 namespace pbs {
