@@ -221,7 +221,7 @@ def main():
     # ---- untimed extras: where the planted keys end up, the inverse permutation with a real sigma, a plain copy
     extras = {}
     if not given and "planted" in w.extra:
-        kidx_h = (pipe.kidx[0] if token_copy else pipe.kidx).cpu().numpy()
+        kidx_h = pipe.kidx.cpu().numpy()
         seg = w.segment
         ranks = []
         for (b, h), pos in w.extra["planted"].items():
@@ -285,8 +285,8 @@ def main():
     # blocks that are multiplied: with the token-order copy, a query block i of a full segment whose list ends with
     # its R own-segment blocks inside one staged chunk of 256 entries takes i % R + 1 blocks for them instead of R
     computed = visited
-    if (token_copy and w.dtype == "bf16" and w.d == 128 and w.block == 128 and w.n % 128 == 0 and
-            (w.batch * w.h_kv + 1) * w.n * 256 < 2 ** 31 - 1):
+    if (token_copy and w.dtype == "bf16" and w.d == 128 and w.block == 128 and
+            (w.batch * w.h_kv * T * 128 + w.n) * 256 < 2 ** 31 - 1):
         R, G = w.segment // w.block, w.n // w.segment
         i = np.arange(T, dtype=np.int64)[None, None, :]
         applies = (i // R < G) & (cnt >= R) & (((cnt - 1) % 256) + 1 >= R)

@@ -65,11 +65,14 @@ typedef enum { PBS_F32 = 0, PBS_BF16 = 1 } pbs_dtype;
 
 /*
  * PBS_FLAG_FORCE_FIRST_BLOCK: Algorithm 2 also keeps key block 0 in every row.
- * PBS_FLAG_TOKEN_ORDER_COPY: K', Vt and kidx are twice as long: behind the permuted tensor of all (batch, kv head)
- *   pairs lies a second one of the same shape in token order (K itself, V block-transposed without permutation,
- *   kidx = 0 .. n-1).  pbs_segment_permute writes both halves; every other stage reads the first half as before,
- *   and pbs_attn_fwd may evaluate a query block's own segment from the second half (see there).  The result is
- *   the same attention: the order in which keys are summed does not matter (Theorem 1).
+ * PBS_FLAG_TOKEN_ORDER_COPY: K', Vt and kidx each carry a second tensor of the same shape in token order (K
+ *   itself, V block-transposed without permutation, kidx = 0 .. n-1) in the same allocation, starting
+ *   batch * h_kv * T * block rows (K': rows of d elements; kidx: entries; Vt: key slots of d elements, i.e. directly
+ *   behind the first tensor) after the start of the permuted one; each buffer therefore holds
+ *   batch * h_kv * (T * block + n) rows (Vt: 2 * batch * h_kv * T * block).  pbs_segment_permute writes both; every
+ *   other stage reads the first tensor as before, and pbs_attn_fwd may evaluate a query block's own segment from
+ *   the second (see there).  The result is the same attention: the order in which keys are summed does not matter
+ *   (Theorem 1).
  */
 enum { PBS_FLAG_FORCE_FIRST_BLOCK = 1u, PBS_FLAG_TOKEN_ORDER_COPY = 2u };
 
@@ -170,9 +173,9 @@ pbs_status pbs_block_mask(const pbs_problem *p, const void *Qp, const void *Kp, 
  *   running-maximum recurrence of Algorithm 1.  The contents of ws need not be initialised and mean nothing afterwards.
  *   Setting the environment variable PBS_ATTN_NARROW (read once per process) sends every query block of that shape
  *   through the second kernel alone; it exists for A/B timing.
- *   With PBS_FLAG_TOKEN_ORDER_COPY (Kp, Vt, kidx carry their token-order halves), qidx == NULL and that same shape, a
+ *   With PBS_FLAG_TOKEN_ORDER_COPY (Kp, Vt, kidx carry their token-order copies), qidx == NULL and that same shape, a
  *   query block inside a full segment whose list ends with all R blocks of its own segment, ascending (as
- *   pbs_block_mask writes them), takes these R blocks from the token-order half instead: the blocks before the
+ *   pbs_block_mask writes them), takes these R blocks from the token-order copy instead: the blocks before the
  *   diagonal in full, the diagonal block under the causal test, none after it.  These are the same visible keys,
  *   so O' and lse are the same up to the rounding order of the sums; every other list is processed as listed.
  */

@@ -103,26 +103,44 @@ def alloc_workspace(p, stage, device="cuda"):
     return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)   # torch allocations are 512-B aligned
 
 
-def halves(p):
-    """1, or 2 when K', Vt and kidx carry a token-order copy behind the permuted tensor (PBS_FLAG_TOKEN_ORDER_COPY);
-    the copies are the leading axis of the tensors allocated here, so x[0] is what every other stage reads."""
-    return 2 if p.flags & FLAG_TOKEN_ORDER_COPY else 1
+def has_token_copy(p):
+    return bool(p.flags & FLAG_TOKEN_ORDER_COPY)
+
+
+def _tok_rows(p):
+    """Rows between the start of a permuted tensor and the start of its token-order copy (PBS_FLAG_TOKEN_ORDER_COPY)."""
+    return p.batch * p.h_kv * T_of(p) * p.block
+
+
+def _alloc_with_copy(p, shape, row_elems, dtype, device):
+    """A [batch, h_kv, ...] tensor; with PBS_FLAG_TOKEN_ORDER_COPY it is the head of a larger allocation whose tail
+    holds the token-order copy (token_copy() returns that view; the storage lives as long as either view does)."""
+    numel = 1
+    for v in shape:
+        numel *= v
+    if not has_token_copy(p):
+        return torch.empty(shape, dtype=dtype, device=device)
+    flat = torch.empty(_tok_rows(p) * row_elems + numel, dtype=dtype, device=device)
+    return flat[:numel].view(shape)
+
+
+def token_copy(p, x, row_elems):
+    """The token-order copy that lies behind a K' (row_elems = d), Vt (d) or kidx (1) tensor from the allocators here."""
+    off = x.storage_offset() + _tok_rows(p) * row_elems
+    return torch.as_strided(x, x.shape, x.stride(), off)
 
 
 def alloc_vt(p, device="cuda"):
     G = min(p.block, 32)                                   # keys per transposed group
-    shape = (p.batch, p.h_kv, T_of(p), p.block // G, p.d, G)
-    return torch.empty((2,) + shape if halves(p) == 2 else shape, dtype=torch_dtype(p), device=device)
+    return _alloc_with_copy(p, (p.batch, p.h_kv, T_of(p), p.block // G, p.d, G), p.d, torch_dtype(p), device)
 
 
 def alloc_kp(p, device="cuda"):
-    shape = (p.batch, p.h_kv, p.n, p.d)
-    return torch.empty((2,) + shape if halves(p) == 2 else shape, dtype=torch_dtype(p), device=device)
+    return _alloc_with_copy(p, (p.batch, p.h_kv, p.n, p.d), p.d, torch_dtype(p), device)
 
 
 def alloc_kidx(p, device="cuda"):
-    shape = (p.batch, p.h_kv, p.n)
-    return torch.empty((2,) + shape if halves(p) == 2 else shape, dtype=torch.int32, device=device)
+    return _alloc_with_copy(p, (p.batch, p.h_kv, p.n), 1, torch.int32, device)
 
 
 def _ws_args(p, stage, ws):

@@ -601,12 +601,12 @@ extern "C" pbs_status pbs_attn_fwd(const pbs_problem *p, const void *Qp, const v
             // on ordinary inputs, then each workgroup of the second launch leaves at once) with the rescaling kernel
             int32_t *redo = narrow_only ? nullptr : reinterpret_cast<int32_t *>(ws);
             if (redo) {
-                // own segments from the token-order halves: identity sigma, whole blocks, and every byte of both
-                // halves of a head within reach of 32-bit buffer offsets
-                const long long rows = (long long)g.batch * g.h_kv * g.n;
-                const bool own_tok = (p->flags & PBS_FLAG_TOKEN_ORDER_COPY) && !qidx && g.n % 128 == 0 &&
-                                     (rows + g.n) * 256 < 0x7fffffffLL;
-                const int tok_delta = own_tok ? (int)(rows / 128) : 0;
+                // own segments from the token-order copies: identity sigma, and every byte of both copies of a head
+                // within reach of 32-bit buffer offsets
+                const long long tok_blocks = (long long)g.batch * g.h_kv * g.T;
+                const bool own_tok = (p->flags & PBS_FLAG_TOKEN_ORDER_COPY) && !qidx &&
+                                     (tok_blocks * 128 + g.n) * 256 < 0x7fffffffLL;
+                const int tok_delta = own_tok ? (int)tok_blocks : 0;
                 st = launch_attn_wide(g, Qp, Kp, Vt, qidx, kidx, row_cnt, col_idx, Op, lse, redo, tok_delta, s);
                 if (st != PBS_OK) return st;
             }

@@ -480,7 +480,7 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     const int32_t *cols = col_idx + ((size_t)bhq * g.T + i) * g.T;
     constexpr int kRawDword = 0x00020000;                  // gfx9 descriptor word 3: raw 32-bit data format
     TileBuffers buf;
-    // tok_delta > 0: a token-order copy of K', Vt and kidx lies tok_delta blocks (all batch * h_kv heads) behind the
+    // tok_delta > 0: a token-order copy of K', Vt and kidx lies tok_delta = batch * h_kv * T blocks behind the
     // permuted one, so block j of this head in token order is block tok_delta + j of the same descriptors
     const int reach = tok_delta * BLOCK + g.n;             // rows within reach of this head's descriptors
     buf.k = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(Kp + bhk * (size_t)g.n * D), 0, reach * 256, kRawDword);

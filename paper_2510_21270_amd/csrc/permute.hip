@@ -247,7 +247,8 @@ extern "C" pbs_status pbs_segment_permute(const pbs_problem *p, const float *sco
     if ((st = launch_status()) != PBS_OK) return st;
     const bool token_copy = (p->flags & PBS_FLAG_TOKEN_ORDER_COPY) != 0;
     const size_t total = (size_t)nbh * g.n;
-    int32_t *kidx_tok = kidx + total;                      // second halves: token order
+    const size_t tok_rows = (size_t)nbh * g.T * g.block;   // the token-order copies start this many rows in
+    int32_t *kidx_tok = kidx + tok_rows;
     if (token_copy) {
         hipLaunchKernelGGL(iota_kernel, dim3(grid_for(total, 256)), dim3(256), 0, s, kidx_tok, g.n, total);
         if ((st = launch_status()) != PBS_OK) return st;
@@ -258,7 +259,7 @@ extern "C" pbs_status pbs_segment_permute(const pbs_problem *p, const float *sco
     const size_t vt_half = (size_t)nbh * g.T * g.d * g.block * es;
     for (int half = 0; half < (token_copy ? 2 : 1); ++half) {
         const int32_t *idx = half ? kidx_tok : kidx;
-        char *kdst = reinterpret_cast<char *>(Kp) + half * total * g.d * es;
+        char *kdst = reinterpret_cast<char *>(Kp) + half * tok_rows * g.d * es;
         char *vdst = reinterpret_cast<char *>(Vt) + half * vt_half;
         hipLaunchKernelGGL(move_rows_kernel<false>, move_grid(g.n, cpr, nbh), dim3(256), 0, s, (const uintx4 *)K,
                            half ? (const int32_t *)nullptr : idx, (uintx4 *)kdst, g.n, ilog2(cpr));

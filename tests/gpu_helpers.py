@@ -56,3 +56,12 @@ def check_close(got, want, dtype, what=""):
     assert err.max() <= tol["max_abs"], "%s max-abs %.3e > %.1e" % (what, err.max(), tol["max_abs"])
     assert err.mean() <= tol["mean_abs"], "%s mean-abs %.3e > %.1e" % (what, err.mean(), tol["mean_abs"])
     return float(err.max()), float(err.mean())
+
+
+def with_token_copy(p, kind, first, second):
+    """A K' ("kp"), Vt ("vt") or kidx ("kidx") tensor of problem p (PBS_FLAG_TOKEN_ORDER_COPY set) holding `first`,
+    with `second` as the token-order copy behind it."""
+    x = {"kp": pbs.alloc_kp, "vt": pbs.alloc_vt, "kidx": pbs.alloc_kidx}[kind](p)
+    x.copy_(first)
+    pbs.token_copy(p, x, 1 if kind == "kidx" else p.d).copy_(second)
+    return x

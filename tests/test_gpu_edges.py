@@ -3,7 +3,8 @@ import numpy as np
 import pytest
 import torch
 
-from gpu_helpers import check_close, i32_dev, make_problem, mask_from_bits, to_dev, to_host, vt_layout
+from gpu_helpers import (check_close, i32_dev, make_problem, mask_from_bits, to_dev, to_host, vt_layout,
+                         with_token_copy)
 from paper_2510_21270_amd import binding as pbs
 from paper_2510_21270_amd import workloads as wl
 
@@ -191,8 +192,9 @@ def test_scores_climbing_far_above_the_first_keys_take_the_second_pass(oracle):
     row_cnt4 = np.tile(((np.arange(T) // R + 1) * R).astype(np.int32), (1, Hq, 1))
     Kd, Vd, kd = to_dev(K, "bf16"), to_dev(vt_layout(V, block), "bf16"), i32_dev(kidx)
     ws.zero_()
-    got4, lse4 = pbs.attn_fwd(p4, to_dev(Q, "bf16"), torch.stack([Kd, Kd]), torch.stack([Vd, Vd]), None,
-                              torch.stack([kd, kd]), i32_dev(row_cnt4), i32_dev(col_idx), want_lse=True, ws=ws)
+    got4, lse4 = pbs.attn_fwd(p4, to_dev(Q, "bf16"), with_token_copy(p4, "kp", Kd, Kd),
+                              with_token_copy(p4, "vt", Vd, Vd), None, with_token_copy(p4, "kidx", kd, kd),
+                              i32_dev(row_cnt4), i32_dev(col_idx), want_lse=True, ws=ws)
     torch.cuda.synchronize()
     assert ws[:Hq * T * 4].view(torch.int32).sum().item() >= Hq * (T - 3)
     check_close(to_host(got4), want, "bf16", "second pass after a first pass on the token-order copy")

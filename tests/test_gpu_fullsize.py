@@ -10,7 +10,8 @@ import numpy as np
 import pytest
 import torch
 
-from gpu_helpers import check_close, i32_dev, make_problem, mask_from_bits, to_dev, to_host, vt_layout
+from gpu_helpers import (check_close, i32_dev, make_problem, mask_from_bits, to_dev, to_host, vt_layout,
+                         with_token_copy)
 from paper_2510_21270_amd import binding as pbs
 from paper_2510_21270_amd import workloads as wl
 
@@ -94,11 +95,11 @@ def test_full_size_attention_on_sampled_rows(oracle, name):
     assert (Op.float().abs() <= bound).all()
     # the same rows with every own segment taken from a token-order copy of K, V'^T and kidx behind the permuted ones
     p2 = make_problem(w, flags=w.flags | pbs.FLAG_TOKEN_ORDER_COPY)
-    Kp2 = torch.stack([Kp_d, st["K"]])
-    Vt2 = torch.stack([Vt_d, to_dev(vt_layout(w.V, w.block), "bf16")])
+    Kp2 = with_token_copy(p2, "kp", Kp_d, st["K"])
+    Vt2 = with_token_copy(p2, "vt", Vt_d, to_dev(vt_layout(w.V, w.block), "bf16"))
     del Kp_d, Vt_d
-    kidx2 = torch.stack([i32_dev(st["kidx"]), torch.arange(w.n, device="cuda", dtype=torch.int32)
-                         .expand(w.batch, w.h_kv, w.n)])
+    kidx2 = with_token_copy(p2, "kidx", i32_dev(st["kidx"]),
+                            torch.arange(w.n, device="cuda", dtype=torch.int32).expand(w.batch, w.h_kv, w.n))
     Op2, lse2 = pbs.attn_fwd(p2, st["Q"], Kp2, Vt2, None, kidx2, i32_dev(st["row_cnt"]), i32_dev(st["col_idx"]),
                              torch.empty_like(Op), want_lse=True)
     torch.cuda.synchronize()
@@ -191,11 +192,10 @@ def test_element_offsets_beyond_32_bits_reproduce_the_last_group_run_on_its_own(
     O1 = small.run(Q[:, Hq - r:].contiguous(), K[:, Hkv - 1:].contiguous(), V[:, Hkv - 1:].contiguous())
     torch.cuda.synchronize()
     assert torch.equal(big.scores[:, Hkv - 1:], small.scores)
-    # with the token-order copy the tensors have a leading axis of two: permuted, token order (offsets up to 1.5e9
-    # bytes from a head's base inside the attention kernel)
-    assert torch.equal(big.kidx[..., Hkv - 1:, :], small.kidx)
-    assert torch.equal(big.Kp[..., Hkv - 1:, :, :], small.Kp)
-    assert torch.equal(big.Vt[..., Hkv - 1:, :, :, :, :], small.Vt)
+    # (with the token-order copy the attention kernel reaches up to 1.5e9 bytes beyond a head's base)
+    assert torch.equal(big.kidx[:, Hkv - 1:], small.kidx)
+    assert torch.equal(big.Kp[:, Hkv - 1:], small.Kp)
+    assert torch.equal(big.Vt[:, Hkv - 1:], small.Vt)
     assert torch.equal(big.mask_bits[:, Hq - r:], small.mask_bits)
     assert torch.equal(big.row_cnt[:, Hq - r:], small.row_cnt)
     T = N // B

@@ -262,9 +262,9 @@ def test_random_shapes_stage_by_stage(lib, oracle, seed, wide):
 @pytest.mark.parametrize("name", ["bf16_even", "bf16_b128", "bf16_b64", "f32_d128"])
 def test_token_order_copy_of_the_own_segment(lib, oracle, name):
     # PBS_FLAG_TOKEN_ORDER_COPY: the permutation stage writes K, V'^T and kidx a second time in token order, and the
-    # 64-queries-per-wave attention kernel takes a query block's own segment from that copy (whole blocks only:
-    # bf16_even; the other cases write the copy and must ignore it).  Same visible keys, so the oracle's O and
-    # lse must be met to the same tolerance; where the copy is ignored the output is bit-identical.
+    # 64-queries-per-wave attention kernel takes a query block's own segment from that copy (bf16_even: whole blocks;
+    # bf16_b128: a ragged last block; the other cases write the copy and must ignore it).  Same visible keys, so the
+    # oracle's O and lse must be met to the same tolerance; where the copy is ignored the output is bit-identical.
     w, res = _oracle_run(oracle, name, False)
     p0 = make_problem(w)
     p1 = make_problem(w, flags=w.flags | pbs.FLAG_TOKEN_ORDER_COPY)
@@ -273,41 +273,41 @@ def test_token_order_copy_of_the_own_segment(lib, oracle, name):
     scores = torch.from_numpy(res["s_handoff"]).cuda()
     kidx, Kp, Vt = pbs.segment_permute(p1, scores, K, V)
     torch.cuda.synchronize()
-    assert kidx.shape[0] == 2 and Kp.shape[0] == 2 and Vt.shape[0] == 2
-    np.testing.assert_array_equal(kidx[0].cpu().numpy(), res["kidx"])
-    np.testing.assert_array_equal(to_host(Kp[0]), res["Kp"].astype(np.float64))
-    np.testing.assert_array_equal(to_host(Vt[0]), vt_layout(res["Vp"], w.block).astype(np.float64))
-    assert torch.equal(kidx[1], torch.arange(w.n, device="cuda", dtype=torch.int32).expand(w.batch, w.h_kv, w.n))
-    assert torch.equal(Kp[1], K)
-    np.testing.assert_array_equal(to_host(Vt[1]), vt_layout(w.V, w.block).astype(np.float64))
-    kidx2, _, _ = pbs.segment_permute(p1, scores, None, None, indices_only=True)
-    assert torch.equal(kidx2, kidx)
-    # selection reads the first halves only
+    np.testing.assert_array_equal(kidx.cpu().numpy(), res["kidx"])
+    np.testing.assert_array_equal(to_host(Kp), res["Kp"].astype(np.float64))
+    np.testing.assert_array_equal(to_host(Vt), vt_layout(res["Vp"], w.block).astype(np.float64))
+    iota = torch.arange(w.n, device="cuda", dtype=torch.int32).expand(w.batch, w.h_kv, w.n)
+    assert torch.equal(pbs.token_copy(p1, kidx, 1), iota)
+    assert torch.equal(pbs.token_copy(p1, Kp, w.d), K)
+    np.testing.assert_array_equal(to_host(pbs.token_copy(p1, Vt, w.d)), vt_layout(w.V, w.block).astype(np.float64))
+    kidx2 = pbs.alloc_kidx(p1)
+    pbs.segment_permute(p1, scores, None, None, kidx=kidx2, indices_only=True)
+    assert torch.equal(kidx2, kidx) and torch.equal(pbs.token_copy(p1, kidx2, 1), iota)
+    # selection reads the permuted tensors only
     bits, cnt, cols = pbs.block_mask(p1, to_dev(res["Qp"], w.dtype), Kp)
     np.testing.assert_array_equal(cnt.cpu().numpy(), res["row_cnt"])
     # attention on the oracle's lists
     Q = to_dev(res["Qp"], w.dtype)
     rc, ci = i32_dev(res["row_cnt"]), i32_dev(res["col_idx"])
     O1, lse1 = pbs.attn_fwd(p1, Q, Kp, Vt, None, kidx, rc, ci, want_lse=True)
-    O0, lse0 = pbs.attn_fwd(p0, Q, Kp[0], Vt[0], None, kidx[0], rc, ci, want_lse=True)
+    O0, lse0 = pbs.attn_fwd(p0, Q, Kp, Vt, None, kidx, rc, ci, want_lse=True)
     torch.cuda.synchronize()
     check_close(to_host(O1), res["Op"], w.dtype, name + " O' with the token-order copy")
     np.testing.assert_allclose(lse1.cpu().numpy(), res["lse"], rtol=0, atol=2e-2 if w.dtype == "bf16" else 1e-4)
-    if name == "bf16_even":
+    if name in ("bf16_even", "bf16_b128"):
         assert not torch.equal(O1, O0)                       # a different order of the sums: the copy was used
         # lists in descending order do not end with the own segment: processed as listed, bit for bit
         T = w.T
-        rev = ci.clone()
         ar = torch.arange(T, device="cuda").view(1, 1, 1, T)
         src = torch.clamp(rc.unsqueeze(-1).long() - 1 - ar, min=0)
         rev = torch.where(ar < rc.unsqueeze(-1), torch.gather(ci, 3, src), ci)
         R1 = pbs.attn_fwd(p1, Q, Kp, Vt, None, kidx, rc, rev)
-        R0 = pbs.attn_fwd(p0, Q, Kp[0], Vt[0], None, kidx[0], rc, rev)
+        R0 = pbs.attn_fwd(p0, Q, Kp, Vt, None, kidx, rc, rev)
         assert torch.equal(R1, R0)
         # a caller-supplied sigma switches the shortcut off as well
         sig = i32_dev(wl.random_segment_perm(5, w.batch * w.h_q, w.n, w.segment).reshape(w.batch, w.h_q, w.n))
         S1 = pbs.attn_fwd(p1, Q, Kp, Vt, sig, kidx, rc, ci)
-        S0 = pbs.attn_fwd(p0, Q, Kp[0], Vt[0], sig, kidx[0], rc, ci)
+        S0 = pbs.attn_fwd(p0, Q, Kp, Vt, sig, kidx, rc, ci)
         assert torch.equal(S1, S0)
     else:
         assert torch.equal(O1, O0) and torch.equal(lse1, lse0)
@@ -319,12 +319,12 @@ def test_token_order_copy_of_the_own_segment(lib, oracle, name):
 
 
 @pytest.mark.parametrize("seed", range(12))
-def test_token_order_copy_on_random_whole_block_shapes(lib, oracle, seed):
-    # seeded shapes made of whole blocks (so that the copy is used): segments of 1 to 8 blocks, with and without an
-    # unpermuted tail, batches of one or two, GQA groups of 1, 2 or 4
+def test_token_order_copy_on_random_shapes(lib, oracle, seed):
+    # seeded shapes on which the copy is used: segments of 1 to 8 blocks, with and without an unpermuted tail, whole
+    # blocks or a ragged last one, batches of one or two, GQA groups of 1, 2 or 4
     rng = np.random.default_rng(3000 + seed)
     segment = int(rng.choice([128, 256, 512, 1024]))
-    n = 128 * int(rng.integers(1, 25))
+    n = 128 * int(rng.integers(1, 25)) + (int(rng.integers(1, 128)) if seed % 3 == 0 else 0)
     h_kv = int(rng.choice([1, 2, 3]))
     h_q = h_kv * int(rng.choice([1, 2, 4]))
     tau = float(rng.choice([0.3, 0.6, 0.9]))
@@ -335,7 +335,7 @@ def test_token_order_copy_on_random_whole_block_shapes(lib, oracle, seed):
     what = "batch=%d n=%d hq=%d hkv=%d segment=%d tau=%g flags=%d" % (w.batch, n, h_q, h_kv, segment, tau, w.flags)
     kidx, Kp, Vt = pbs.segment_permute(p, torch.from_numpy(res["s_handoff"]).cuda(), to_dev(w.K, "bf16"),
                                        to_dev(w.V, "bf16"))
-    np.testing.assert_array_equal(kidx[0].cpu().numpy(), res["kidx"], err_msg=what)
+    np.testing.assert_array_equal(kidx.cpu().numpy(), res["kidx"], err_msg=what)
     bits, cnt, cols = pbs.block_mask(p, to_dev(res["Qp"], "bf16"), Kp)
     np.testing.assert_array_equal(mask_from_bits(bits, w.T), res["mask"], err_msg=what)
     np.testing.assert_array_equal(cnt.cpu().numpy(), res["row_cnt"], err_msg=what)
