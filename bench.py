@@ -23,7 +23,7 @@ sys.path.insert(0, ROOT)
 MFMA_BF16_PEAK_TFLOPS = 2500.0       # MI355X dense bf16 matrix peak
 # HBM bytes per pbs_attn_fwd launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same counters
 # read for a plain 1 GiB copy (profiles/bench_c3_hbm_traffic.md); only known for the workloads listed here.
-ATTN_TRAFFIC_BYTES = {"c3": 12317827 * 2.0 * 1024 * (1048576 / 524335 / 2.0) + 1048938 * 1024.0}
+ATTN_TRAFFIC_BYTES = {"c3": 9560389 * 2.0 * 1024 * (1048576 / 524335 / 2.0) + 1048933 * 1024.0}
 HBM_PEAK_GBS = 8000.0                # MI355X HBM3E
 
 
@@ -133,11 +133,12 @@ def main():
     ap.add_argument("--coverage", action="store_true",
                     help="after the timed region, also report the true attention mass inside the selected blocks "
                          "(two more attention passes, one of them over every admitted block)")
-    ap.add_argument("--token-order-copy", action="store_true",
-                    help="set PBS_FLAG_TOKEN_ORDER_COPY: the permutation stage also writes K, V'^T and kidx in token "
-                         "order (twice the bytes of that stage), and the attention evaluates every query block's own "
-                         "segment from that copy: the blocks up to the diagonal, only the diagonal one under the causal "
-                         "test (the same visible keys as the R permuted blocks of the segment, so the same output)")
+    ap.add_argument("--no-token-order-copy", action="store_true",
+                    help="do not set PBS_FLAG_TOKEN_ORDER_COPY.  By default the permutation stage also writes K, V'^T "
+                         "and kidx in token order (twice the bytes of that stage), and the attention evaluates every "
+                         "query block's own segment from that copy: the blocks up to the diagonal, only the diagonal "
+                         "one under the causal test (the same visible keys as the R permuted blocks of the segment, so "
+                         "the same output)")
     ap.add_argument("--dense-baseline", action="store_true",
                     help="after the timed region, also time plain causal attention in token order through the same "
                          "kernel (three more attention passes) and report the sparse layer's speed-up over it")
@@ -163,7 +164,7 @@ def main():
         w.extra = {k: v for k, v in w.extra.items() if k != "planted"}      # keyed by kv head
         w.h_kv, w.name = w.h_q, w.name + "_replicated_kv"
     given = "row_cnt" in w.extra                      # config 5: caller-supplied block lists, identity key order
-    token_copy = args.token_order_copy and not given
+    token_copy = not (args.no_token_order_copy or given)
     flags = w.flags | (pbs.FLAG_TOKEN_ORDER_COPY if token_copy else 0)
     p = pbs.problem(w.batch, w.h_q, w.h_kv, w.n, w.d, w.block, w.segment, w.dtype, tau=w.tau, flags=flags)
     Q, K, V = to_dev(w.Q, w.dtype), to_dev(w.K, w.dtype), to_dev(w.V, w.dtype)
@@ -303,6 +304,8 @@ def main():
     }
     if given:
         alg_bytes = {"segment_permute": alg_bytes["segment_permute"] - w.batch * w.h_kv * w.n * 4}
+    if token_copy:                                     # K and V are read and written a second time, kidx written twice
+        alg_bytes["segment_permute"] += 2 * kv_bytes + w.batch * w.h_kv * w.n * 4
     attn_tflops = flop / (stage_ms["attn_fwd"] * 1e-3) / 1e12
     out = {
         "metric": "pbs_attn_prefill_effective_tflops", "value": flop / (ms_per_step * 1e-3) / 1e12, "unit": "TFLOP/s",
