@@ -75,10 +75,14 @@ __global__ __launch_bounds__(256) void iota_kernel(int32_t *__restrict__ idx, in
 // SCATTER = true : dst[head(row), idx[row]] = src[row]     (O = P^T O')
 // idx == NULL is the identity.  An index outside [0, n) gives a zero row (gather) or is dropped (scatter).
 // ---------------------------------------------------------------------------------------------
+// copy_stride > 0 (gather only): the grid is twice as wide; odd workgroups write a plain copy of the same range of
+// rows copy_stride chunks behind dst (the token-order copy), right next in time to the even workgroup that gathers
+// rows of the same segments, so that most of what they read is still in the last-level caches.
 template <bool SCATTER>
 __global__ __launch_bounds__(256) void move_rows_kernel(const uintx4 *__restrict__ src,
                                                         const int32_t *__restrict__ idx,
-                                                        uintx4 *__restrict__ dst, int n, int cpr_log2)
+                                                        uintx4 *__restrict__ dst, int n, int cpr_log2,
+                                                        size_t copy_stride)
 {
     // grid = (x, nbh): blockIdx.y is the head; workgroup x owns a contiguous range of that head's n * cpr chunks and
     // moves it in batches of U x 256 chunks: all index loads of a batch, then all data loads, then all stores, so
@@ -87,12 +91,14 @@ __global__ __launch_bounds__(256) void move_rows_kernel(const uintx4 *__restrict
     const size_t head = (size_t)blockIdx.y * n;
     const uint32_t chunks = (uint32_t)n << cpr_log2;
     const uint32_t cmask = (1u << cpr_log2) - 1u;
+    const bool plain = copy_stride != 0 && (blockIdx.x & 1);
+    const uint32_t wg = copy_stride ? blockIdx.x >> 1 : blockIdx.x, nwg = copy_stride ? gridDim.x >> 1 : gridDim.x;
     const uintx4 *hsrc = src + (head << cpr_log2);
-    uintx4 *hdst = dst + (head << cpr_log2);
-    const int32_t *hidx = idx ? idx + head : nullptr;
+    uintx4 *hdst = dst + (head << cpr_log2) + (plain ? copy_stride : 0);
+    const int32_t *hidx = (idx && !plain) ? idx + head : nullptr;
     const uint32_t batch = U * 256;
-    const uint32_t per = ((chunks + gridDim.x - 1) / gridDim.x + batch - 1) / batch * batch;
-    const uint32_t begin = min(blockIdx.x * per, chunks), end = min(begin + per, chunks);
+    const uint32_t per = ((chunks + nwg - 1) / nwg + batch - 1) / batch * batch;
+    const uint32_t begin = min(wg * per, chunks), end = min(begin + per, chunks);
     for (uint32_t c0 = begin + threadIdx.x; c0 < end; c0 += batch) {
         int32_t other[U];
         uintx4 v[U];
@@ -126,16 +132,21 @@ __global__ __launch_bounds__(256) void move_rows_kernel(const uintx4 *__restrict
 // 64 / gpp word columns, which then fall into 64 different banks.
 // E = storage type (2 or 4 bytes); VEC = elements per 16-byte chunk.
 // ---------------------------------------------------------------------------------------------
+// copy_stride > 0: the grid is twice as wide; odd workgroups transpose the same key block without the permutation
+// into the copy copy_stride elements behind Vt (see move_rows_kernel).
 template <typename E>
 __global__ __launch_bounds__(256) void gather_vt_kernel(const E *__restrict__ V, const int32_t *__restrict__ kidx,
-                                                        E *__restrict__ Vt, int n, int d, int block, int T)
+                                                        E *__restrict__ Vt, int n, int d, int block, int T,
+                                                        size_t copy_stride)
 {
     constexpr int VEC = 16 / sizeof(E);
     extern __shared__ __align__(16) unsigned char smem_raw[];
     uint32_t *tile = reinterpret_cast<uint32_t *>(smem_raw);
     const int roww = d * (int)sizeof(E) / 4;               // 4-byte words per row
-    const int j = blockIdx.x;
+    const bool plain = copy_stride != 0 && (blockIdx.x & 1);
+    const int j = copy_stride ? blockIdx.x >> 1 : blockIdx.x;
     const size_t bh = blockIdx.y;
+    if (plain) kidx = nullptr;
     const int cpr = d / VEC;
     const int G = vt_group(block);                         // keys per transposed group
     const int gpp = G / VEC;                               // 16-byte pieces per Vt row
@@ -168,7 +179,7 @@ __global__ __launch_bounds__(256) void gather_vt_kernel(const E *__restrict__ V,
         }
     }
     __syncthreads();
-    E *out = Vt + (bh * T + j) * (size_t)d * block;
+    E *out = Vt + (bh * T + j) * (size_t)d * block + (plain ? copy_stride : 0);
     for (int c = threadIdx.x; c < roww * (block / VEC); c += blockDim.x) {
         const int kgi = c % gpp, w = (c / gpp) % roww, gi = c / (gpp * roww);
         const int kg = gi * gpp + kgi;                     // word column w of the rows kg*VEC .. kg*VEC+VEC-1
@@ -256,26 +267,25 @@ extern "C" pbs_status pbs_segment_permute(const pbs_problem *p, const float *sco
     if (!Kp) return PBS_OK;
     const size_t es = elem_size(p->dtype);
     const int cpr = (int)(g.d * es / 16);
-    const size_t vt_half = (size_t)nbh * g.T * g.d * g.block * es;
-    for (int half = 0; half < (token_copy ? 2 : 1); ++half) {
-        const int32_t *idx = half ? kidx_tok : kidx;
-        char *kdst = reinterpret_cast<char *>(Kp) + half * tok_rows * g.d * es;
-        char *vdst = reinterpret_cast<char *>(Vt) + half * vt_half;
-        hipLaunchKernelGGL(move_rows_kernel<false>, move_grid(g.n, cpr, nbh), dim3(256), 0, s, (const uintx4 *)K,
-                           half ? (const int32_t *)nullptr : idx, (uintx4 *)kdst, g.n, ilog2(cpr));
-        if ((st = launch_status()) != PBS_OK) return st;
-        if (p->dtype == PBS_BF16) {
-            const size_t lds = (size_t)g.block * g.d * 2 + (size_t)(g.block / 8) * (64 / (vt_group(g.block) / 8)) * 4;   // tile + skew
-            hipLaunchKernelGGL(gather_vt_kernel<uint16_t>, dim3(g.T, nbh), dim3(256), lds, s, (const uint16_t *)V, idx,
-                               (uint16_t *)vdst, g.n, g.d, g.block, g.T);
-        } else {
-            const size_t lds = (size_t)g.block * g.d * 4 + (size_t)(g.block / 4) * (64 / (vt_group(g.block) / 4)) * 4;
-            hipLaunchKernelGGL(gather_vt_kernel<uint32_t>, dim3(g.T, nbh), dim3(256), lds, s, (const uint32_t *)V, idx,
-                               (uint32_t *)vdst, g.n, g.d, g.block, g.T);
-        }
-        if ((st = launch_status()) != PBS_OK) return st;
+    const size_t vt_half = (size_t)nbh * g.T * g.d * g.block;           // elements
+    dim3 mg = move_grid(g.n, cpr, nbh);
+    if (token_copy) mg.x *= 2;
+    hipLaunchKernelGGL(move_rows_kernel<false>, mg, dim3(256), 0, s, (const uintx4 *)K, (const int32_t *)kidx,
+                       (uintx4 *)Kp, g.n, ilog2(cpr), token_copy ? tok_rows * cpr : (size_t)0);
+    if ((st = launch_status()) != PBS_OK) return st;
+    const dim3 vg(token_copy ? 2 * g.T : g.T, nbh);
+    if (p->dtype == PBS_BF16) {
+        const size_t lds = (size_t)g.block * g.d * 2 + (size_t)(g.block / 8) * (64 / (vt_group(g.block) / 8)) * 4;   // tile + skew
+        hipLaunchKernelGGL(gather_vt_kernel<uint16_t>, vg, dim3(256), lds, s, (const uint16_t *)V,
+                           (const int32_t *)kidx, (uint16_t *)Vt, g.n, g.d, g.block, g.T,
+                           token_copy ? vt_half : (size_t)0);
+    } else {
+        const size_t lds = (size_t)g.block * g.d * 4 + (size_t)(g.block / 4) * (64 / (vt_group(g.block) / 4)) * 4;
+        hipLaunchKernelGGL(gather_vt_kernel<uint32_t>, vg, dim3(256), lds, s, (const uint32_t *)V,
+                           (const int32_t *)kidx, (uint32_t *)Vt, g.n, g.d, g.block, g.T,
+                           token_copy ? vt_half : (size_t)0);
     }
-    return PBS_OK;
+    return launch_status();
 }
 
 extern "C" pbs_status pbs_permute_rows(const pbs_problem *p, int32_t heads, const void *X, const int32_t *idx,
@@ -288,7 +298,7 @@ extern "C" pbs_status pbs_permute_rows(const pbs_problem *p, int32_t heads, cons
     if (!aligned16(X) || !aligned16(Xp) || X == Xp) return PBS_ERR_SHAPE;
     const int cpr = (int)(p->d * elem_size(p->dtype) / 16);
     hipLaunchKernelGGL(move_rows_kernel<false>, move_grid(p->n, cpr, p->batch * heads), dim3(256), 0,
-                       (hipStream_t)stream, (const uintx4 *)X, idx, (uintx4 *)Xp, p->n, ilog2(cpr));
+                       (hipStream_t)stream, (const uintx4 *)X, idx, (uintx4 *)Xp, p->n, ilog2(cpr), (size_t)0);
     return launch_status();
 }
 
@@ -301,6 +311,6 @@ extern "C" pbs_status pbs_unpermute(const pbs_problem *p, const void *Op, const 
     if (Op == O) return qidx ? PBS_ERR_SHAPE : PBS_OK;     // in place only for the identity
     const int cpr = (int)(p->d * elem_size(p->dtype) / 16);
     hipLaunchKernelGGL(move_rows_kernel<true>, move_grid(p->n, cpr, p->batch * p->h_q), dim3(256), 0,
-                       (hipStream_t)stream, (const uintx4 *)Op, qidx, (uintx4 *)O, p->n, ilog2(cpr));
+                       (hipStream_t)stream, (const uintx4 *)Op, qidx, (uintx4 *)O, p->n, ilog2(cpr), (size_t)0);
     return launch_status();
 }
