@@ -15,13 +15,19 @@ namespace pbs {
 // a workgroup barrier.
 // grid = (G + 1, batch*h_kv); workgroup G writes the identity for the unpermuted tail.
 // ---------------------------------------------------------------------------------------------
+// identity != NULL: the positions 0 .. n-1 are written there as well (the kidx of a token-order copy).
 __global__ __launch_bounds__(1024) void segment_argsort_kernel(const float *__restrict__ scores,
-                                                               int32_t *__restrict__ kidx, int n, int segment,
+                                                               int32_t *__restrict__ kidx,
+                                                               int32_t *__restrict__ identity, int n, int segment,
                                                                int G, int p2)
 {
     extern __shared__ uint64_t keys[];
     const int g = blockIdx.x;
     const size_t base = (size_t)blockIdx.y * n;
+    if (identity) {
+        const int lo = g * segment, hi = g >= G ? n : lo + segment;
+        for (int p = lo + threadIdx.x; p < hi; p += blockDim.x) identity[base + p] = p;
+    }
     if (g >= G) {
         for (int p = G * segment + threadIdx.x; p < n; p += blockDim.x) kidx[base + p] = p;
         return;
@@ -63,10 +69,13 @@ __global__ __launch_bounds__(1024) void segment_argsort_kernel(const float *__re
         kidx[base + (size_t)g * segment + t] = g * segment + (int32_t)(keys[t] & 0xffffffffu);
 }
 
-__global__ __launch_bounds__(256) void iota_kernel(int32_t *__restrict__ idx, int n, size_t total)
+__global__ __launch_bounds__(256) void iota_kernel(int32_t *__restrict__ idx, int32_t *__restrict__ idx2, int n,
+                                                   size_t total)
 {
-    for (size_t p = (size_t)blockIdx.x * blockDim.x + threadIdx.x; p < total; p += (size_t)gridDim.x * blockDim.x)
+    for (size_t p = (size_t)blockIdx.x * blockDim.x + threadIdx.x; p < total; p += (size_t)gridDim.x * blockDim.x) {
         idx[p] = (int32_t)(p % (size_t)n);
+        if (idx2) idx2[p] = (int32_t)(p % (size_t)n);
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -245,25 +254,20 @@ extern "C" pbs_status pbs_segment_permute(const pbs_problem *p, const float *sco
     const Geo g = make_geo(p);
     hipStream_t s = (hipStream_t)stream;
     const int nbh = g.batch * g.h_kv;
+    const bool token_copy = (p->flags & PBS_FLAG_TOKEN_ORDER_COPY) != 0;
+    const size_t tok_rows = (size_t)nbh * g.T * g.block;   // the token-order copies start this many rows in
+    int32_t *kidx_tok = token_copy ? kidx + tok_rows : nullptr;
     if (scores) {
         int p2 = 1;
         while (p2 < g.segment) p2 <<= 1;
         const int threads = p2 / 2 < 64 ? 64 : (p2 / 2 > 1024 ? 1024 : p2 / 2);
         hipLaunchKernelGGL(segment_argsort_kernel, dim3(g.G + 1, nbh), dim3(threads), (size_t)p2 * sizeof(uint64_t), s,
-                           scores, kidx, g.n, g.segment, g.G, p2);
+                           scores, kidx, kidx_tok, g.n, g.segment, g.G, p2);
     } else {
         const size_t total = (size_t)nbh * g.n;
-        hipLaunchKernelGGL(iota_kernel, dim3(grid_for(total, 256)), dim3(256), 0, s, kidx, g.n, total);
+        hipLaunchKernelGGL(iota_kernel, dim3(grid_for(total, 256)), dim3(256), 0, s, kidx, kidx_tok, g.n, total);
     }
     if ((st = launch_status()) != PBS_OK) return st;
-    const bool token_copy = (p->flags & PBS_FLAG_TOKEN_ORDER_COPY) != 0;
-    const size_t total = (size_t)nbh * g.n;
-    const size_t tok_rows = (size_t)nbh * g.T * g.block;   // the token-order copies start this many rows in
-    int32_t *kidx_tok = kidx + tok_rows;
-    if (token_copy) {
-        hipLaunchKernelGGL(iota_kernel, dim3(grid_for(total, 256)), dim3(256), 0, s, kidx_tok, g.n, total);
-        if ((st = launch_status()) != PBS_OK) return st;
-    }
     if (!Kp) return PBS_OK;
     const size_t es = elem_size(p->dtype);
     const int cpr = (int)(g.d * es / 16);
