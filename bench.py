@@ -23,7 +23,7 @@ sys.path.insert(0, ROOT)
 MFMA_BF16_PEAK_TFLOPS = 2500.0       # MI355X dense bf16 matrix peak
 # HBM bytes per pbs_attn_fwd launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same counters
 # read for a plain 1 GiB copy (profiles/bench_c3_hbm_traffic.md); only known for the workloads listed here.
-ATTN_TRAFFIC_BYTES = {"c3": 9560389 * 2.0 * 1024 * (1048576 / 524335 / 2.0) + 1048933 * 1024.0}
+ATTN_TRAFFIC_BYTES = {"c3": 9498497 * 2.0 * 1024 * (1048576 / 524335 / 2.0) + 1048919 * 1024.0}
 HBM_PEAK_GBS = 8000.0                # MI355X HBM3E
 
 
