@@ -286,8 +286,9 @@ def main():
     # blocks that are multiplied: with the token-order copy, a query block i of a full segment whose list ends with
     # its R own-segment blocks inside one staged chunk of 256 entries takes i % R + 1 blocks for them instead of R
     computed = visited
-    if (token_copy and w.dtype == "bf16" and w.d == 128 and w.block == 128 and
-            (w.batch * w.h_kv * T * 128 + w.n) * 256 < 2 ** 31 - 1):
+    own_in_token_order = (token_copy and w.dtype == "bf16" and w.d == 128 and w.block == 128 and
+                          (w.batch * w.h_kv * T * 128 + w.n) * 256 < 2 ** 31 - 1)   # what pbs_attn_fwd requires for it
+    if own_in_token_order:
         R, G = w.segment // w.block, w.n // w.segment
         i = np.arange(T, dtype=np.int64)[None, None, :]
         applies = (i // R < G) & (cnt >= R) & (((cnt - 1) % 256) + 1 >= R)
@@ -313,7 +314,8 @@ def main():
         "ms_per_layer": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
         "config": dict(w.describe(), visited_blocks=visited, causal_blocks=causal_total,
-                       own_segment_in_token_order=bool(token_copy), computed_blocks=computed,
+                       token_order_copy=bool(token_copy), own_segment_in_token_order=bool(own_in_token_order),
+                       computed_blocks=computed,
                        density_vs_causal=visited / causal_total, given_mask=bool(given),
                        permuted=not (given or args.no_permute)),
         "stages_ms": stage_ms,
