@@ -284,14 +284,14 @@ def main():
     visited = int(cnt.sum())                           # blocks the masks list
     T = w.T
     # blocks that are multiplied: with the token-order copy, a query block i of a full segment whose list ends with
-    # its R own-segment blocks inside one staged chunk of 256 entries takes i % R + 1 blocks for them instead of R
+    # its R own-segment blocks inside one staged chunk of 1024 entries takes i % R + 1 blocks for them instead of R
     computed = visited
     own_in_token_order = (token_copy and w.dtype == "bf16" and w.d == 128 and w.block == 128 and
                           (w.batch * w.h_kv * T * 128 + w.n) * 256 < 2 ** 31 - 1)   # what pbs_attn_fwd requires for it
     if own_in_token_order:
         R, G = w.segment // w.block, w.n // w.segment
         i = np.arange(T, dtype=np.int64)[None, None, :]
-        applies = (i // R < G) & (cnt >= R) & (((cnt - 1) % 256) + 1 >= R)
+        applies = (i // R < G) & (cnt >= R) & (((cnt - 1) % 1024) + 1 >= R)
         computed = int(visited - np.where(applies, R - (i % R + 1), 0).sum())
     causal_total = w.batch * w.h_q * T * (T + 1) // 2
     flop = computed * 4.0 * w.block * w.block * w.d     # effective TFLOP/s counts computed blocks only

@@ -35,7 +35,7 @@ constexpr int BLOCK = 128, D = 128;
 constexpr int KS = 32;                                     // keys per sub-tile
 constexpr int kStageB = 8192;                              // K' sub-tile: 32 rows x 256 B; V'^T sub-tile: 128 rows x 64 B
 constexpr int kLoadsPerWave = 8;                           // 16-byte-per-lane loads a wave issues per stage
-constexpr int kList = 256;                                 // listed blocks staged in LDS at a time
+constexpr int kList = 1024;                                // listed blocks staged in LDS at a time
 constexpr int kXcds = 8, kCohort = 64;
 constexpr float kLog2eF = 1.4426950408889634f;
 constexpr float kLn2F = 0.6931471805599453f;
