@@ -287,7 +287,7 @@ def main():
     # its R own-segment blocks inside one staged chunk of 1024 entries takes i % R + 1 blocks for them instead of R
     computed = visited
     own_in_token_order = (token_copy and w.dtype == "bf16" and w.d == 128 and w.block == 128 and
-                          (w.batch * w.h_kv * T * 128 + w.n) * 256 < 2 ** 31 - 1)   # what pbs_attn_fwd requires for it
+                          (w.batch * w.h_kv + 1) * T * 128 * 256 < 2 ** 31 - 1)   # what pbs_attn_fwd requires for it
     if own_in_token_order:
         R, G = w.segment // w.block, w.n // w.segment
         i = np.arange(T, dtype=np.int64)[None, None, :]

@@ -605,7 +605,7 @@ extern "C" pbs_status pbs_attn_fwd(const pbs_problem *p, const void *Qp, const v
                 // within reach of 32-bit buffer offsets
                 const long long tok_blocks = (long long)g.batch * g.h_kv * g.T;
                 const bool own_tok = (p->flags & PBS_FLAG_TOKEN_ORDER_COPY) && !qidx &&
-                                     (tok_blocks * 128 + g.n) * 256 < 0x7fffffffLL;
+                                     (tok_blocks + g.T) * 128 * 256 < 0x7fffffffLL;
                 const int tok_delta = own_tok ? (int)tok_blocks : 0;
                 st = launch_attn_wide(g, Qp, Kp, Vt, qidx, kidx, row_cnt, col_idx, Op, lse, redo, tok_delta, s);
                 if (st != PBS_OK) return st;
