@@ -507,7 +507,7 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         }
         __syncthreads();
         // Own segment in token order: when the list ends with all blocks jmask .. ni - 1 of the query block's own
-        // (full) segment, ascending, they are replaced by the token-order blocks jmask .. i of the second halves.
+        // (full) segment, ascending, they are replaced by the blocks jmask .. i of the token-order copies.
         // Keys of a segment are the same set in either order, so the visible keys are the same; in token order
         // the blocks before the diagonal need no mask and those after it hold no visible key.
         if (tok_delta > 0 && i / g.R < g.G && base + len == cnt && len >= ni - jmask) {
