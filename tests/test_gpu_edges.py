@@ -245,11 +245,13 @@ def test_matrix_rate_probe_runs_and_counts_its_work():
     assert pbs.mfma_rate_probe(True, iters=2000, reps=1) > 100.0
 
 
-def test_pipeline_replayed_from_a_hip_graph_matches_eager_runs():
+@pytest.mark.parametrize("extra_flags", [0, pbs.FLAG_TOKEN_ORDER_COPY])
+def test_pipeline_replayed_from_a_hip_graph_matches_eager_runs(extra_flags):
     # the five calls captured once; every replay, with new inputs copied into the captured tensors and eager work and
-    # synchronisations in between, must reproduce the eager pipeline bit for bit
+    # synchronisations in between, must reproduce the eager pipeline bit for bit (also in the configuration bench.py
+    # times, with the token-order copy)
     w = wl.planted("graph", 21, 4, 2, 2048 + 45, 128, 128, 512, 0.9, "bf16", 8, rope_base=5e5)
-    p = make_problem(w)
+    p = make_problem(w, flags=w.flags | extra_flags)
     eager, graphed = pbs.Pipeline(p), pbs.Pipeline(p)
     Q, K, V = to_dev(w.Q, "bf16"), to_dev(w.K, "bf16"), to_dev(w.V, "bf16")
     Qs, Ks, Vs = Q.clone(), K.clone(), V.clone()
