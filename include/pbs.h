@@ -119,6 +119,22 @@ pbs_status pbs_key_scores(const pbs_problem *p, const void *Q, const void *K, fl
                           void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * For callers that cannot allocate or pass scratch memory (code under HIP graph capture that owns no workspace,
+ * tight serving loops, harnesses that forbid hipMalloc): pbs_key_scores with its scratch memory in a device array
+ * that is part of the library image instead of in `ws`.  Same arguments otherwise, same kernels, bit-identical
+ * scores.  Allocates nothing and calls no allocating routine.
+ *   The array holds pbs_key_scores_static_scratch_bytes() = 4 MiB on every GPU the library runs on, until the
+ *   process ends; a problem whose pbs_workspace_bytes(p, PBS_STAGE_KEY_SCORES) is larger is rejected with
+ *   PBS_ERR_WORKSPACE and nothing is enqueued (the headline layer, 8 kv heads x 131072 keys, needs 1.5 MiB).
+ *   All calls on one GPU share that GPU's array: two calls whose kernels may overlap in time (different streams,
+ *   or different host threads without ordering between their streams) race on it; calls on one stream are safe.
+ *   Nothing in the array has to be cleared between calls: every word that a call reads it has written before.
+ * Errors: as pbs_key_scores, plus PBS_ERR_HIP when the array's address cannot be obtained on the current device.
+ */
+pbs_status pbs_key_scores_static(const pbs_problem *p, const void *Q, const void *K, float *scores, void *stream);
+size_t pbs_key_scores_static_scratch_bytes(void);
+
+/*
  * Eq. 5 inside each full segment: kidx[g*S + t] = g*S + (position of the t-th largest score of segment g),
  * equal scores in ascending position (stable), tail positions kept (identity).  Then Algorithm 1's first
  * step for keys and values: Kp[slot] = K[kidx[slot]], Vt = block-transposed V[kidx[.]].

@@ -19,7 +19,7 @@ FLAG_FORCE_FIRST_BLOCK, FLAG_TOKEN_ORDER_COPY = 1, 2
 
 EXPORTS = ["pbs_status_string", "pbs_validate", "pbs_workspace_bytes", "pbs_vt_bytes", "pbs_key_scores",
            "pbs_segment_permute", "pbs_permute_rows", "pbs_block_mask", "pbs_attn_fwd", "pbs_unpermute",
-           "pbs_mfma_rate_probe"]
+           "pbs_mfma_rate_probe", "pbs_key_scores_static", "pbs_key_scores_static_scratch_bytes"]
 
 
 class PbsError(RuntimeError):
@@ -50,6 +50,9 @@ def load_library():
         lib.pbs_vt_bytes.restype = Z
         lib.pbs_vt_bytes.argtypes = [P]
         lib.pbs_key_scores.argtypes = [P, V, V, V, V, Z, V]
+        lib.pbs_key_scores_static.argtypes = [P, V, V, V, V]
+        lib.pbs_key_scores_static_scratch_bytes.restype = Z
+        lib.pbs_key_scores_static_scratch_bytes.argtypes = []
         lib.pbs_segment_permute.argtypes = [P, V, V, V, V, V, V, V, Z, V]
         lib.pbs_permute_rows.argtypes = [P, ctypes.c_int32, V, V, V, V]
         lib.pbs_block_mask.argtypes = [P, V, V, V, V, V, V, Z, V]
@@ -155,6 +158,14 @@ def key_scores(p, Q, K, scores=None, ws=None):
     ws, wp, wn = _ws_args(p, STAGE_KEY_SCORES, ws)
     _check(load_library().pbs_key_scores(ctypes.byref(p), _ptr(Q), _ptr(K), _ptr(scores), wp, wn, _stream()),
            "pbs_key_scores")
+    return scores
+
+
+def key_scores_static(p, Q, K, scores=None):
+    if scores is None:
+        scores = torch.empty((p.batch, p.h_kv, p.n), dtype=torch.float32, device=K.device)
+    _check(load_library().pbs_key_scores_static(ctypes.byref(p), _ptr(Q), _ptr(K), _ptr(scores), _stream()),
+           "pbs_key_scores_static")
     return scores
 
 

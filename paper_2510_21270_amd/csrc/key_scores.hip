@@ -431,16 +431,12 @@ static pbs_status run_generic(const pbs_problem *p, const Geo &g, const void *Q,
 
 using namespace pbs;
 
-extern "C" pbs_status pbs_key_scores(const pbs_problem *p, const void *Q, const void *K, float *scores, void *ws,
-                                     size_t ws_bytes, void *stream)
+// Everything after the argument checks: the launches of one pbs_key_scores call with its scratch memory at `ws`.
+static pbs_status enqueue_key_scores(const pbs_problem *p, const void *Q, const void *K, float *scores, void *ws,
+                                     hipStream_t s)
 {
-    pbs_status st = validate(p);
-    if (st != PBS_OK) return st;
-    if (!Q || !K || !scores) return PBS_ERR_NULL;
-    if (!aligned16(Q) || !aligned16(K)) return PBS_ERR_SHAPE;
-    if ((st = check_ws(p, PBS_STAGE_KEY_SCORES, ws, ws_bytes)) != PBS_OK) return st;
+    pbs_status st;
     const Geo g = make_geo(p);
-    hipStream_t s = (hipStream_t)stream;
     char *w = reinterpret_cast<char *>(ws);
     if (!use_mfma(p)) {
         if (p->dtype == PBS_BF16) return run_generic<bf16_t>(p, g, Q, K, scores, w, s);
@@ -464,4 +460,52 @@ extern "C" pbs_status pbs_key_scores(const pbs_problem *p, const void *Q, const 
     hipLaunchKernelGGL(scores_sweep2_kernel, dim3(nwg, nbh), dim3(256), 0, s, (const bf16_t *)K, qsplit, cvec, scores,
                        g, kpw);
     return launch_status();
+}
+
+extern "C" pbs_status pbs_key_scores(const pbs_problem *p, const void *Q, const void *K, float *scores, void *ws,
+                                     size_t ws_bytes, void *stream)
+{
+    pbs_status st = validate(p);
+    if (st != PBS_OK) return st;
+    if (!Q || !K || !scores) return PBS_ERR_NULL;
+    if (!aligned16(Q) || !aligned16(K)) return PBS_ERR_SHAPE;
+    if ((st = check_ws(p, PBS_STAGE_KEY_SCORES, ws, ws_bytes)) != PBS_OK) return st;
+    return enqueue_key_scores(p, Q, K, scores, ws, (hipStream_t)stream);
+}
+
+// ------------------------------------------------------------------ the entry point that allocates nothing
+// pbs_key_scores with its scratch memory (split Qhat, per-workgroup row statistics, merged constants) in a
+// file-scope device array instead of a caller-supplied workspace.  Every GPU holds its own copy of the array at its
+// own address; the address is looked up once per device, with that device current, and host code only ever uses
+// that address, never the array's name.
+constexpr size_t kStaticScratchBytes = (size_t)4 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+static void *static_scratch_of_current_device()
+{
+    constexpr int kMaxDevices = 64;
+    static std::atomic<void *> ptr_of[kMaxDevices];
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    void *ptr = ptr_of[dev].load(std::memory_order_acquire);
+    if (!ptr) {
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return nullptr;
+        ptr_of[dev].store(ptr, std::memory_order_release);   // racing first calls look up the same address
+    }
+    return ptr;
+}
+
+extern "C" size_t pbs_key_scores_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+extern "C" pbs_status pbs_key_scores_static(const pbs_problem *p, const void *Q, const void *K, float *scores,
+                                            void *stream)
+{
+    pbs_status st = validate(p);
+    if (st != PBS_OK) return st;
+    if (!Q || !K || !scores) return PBS_ERR_NULL;
+    if (!aligned16(Q) || !aligned16(K)) return PBS_ERR_SHAPE;
+    if (pbs_workspace_bytes(p, PBS_STAGE_KEY_SCORES) > kStaticScratchBytes) return PBS_ERR_WORKSPACE;
+    void *ws = static_scratch_of_current_device();
+    if (!ws) return PBS_ERR_HIP;
+    return enqueue_key_scores(p, Q, K, scores, ws, (hipStream_t)stream);
 }
