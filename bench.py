@@ -21,10 +21,22 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0       # MI355X dense bf16 matrix peak
-# HBM bytes per pbs_attn_fwd launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same counters
-# read for a plain 1 GiB copy (profiles/bench_c3_hbm_traffic.md); only known for the workloads listed here.
-ATTN_TRAFFIC_BYTES = {"c3": 9498497 * 2.0 * 1024 * (1048576 / 524335 / 2.0) + 1048919 * 1024.0}
 HBM_PEAK_GBS = 8000.0                # MI355X HBM3E
+
+
+def measured_attn_traffic(workload):
+    """HBM bytes per pbs_attn_fwd launch as measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE, scaled by what the
+    same counters read for a plain copy of known size): read from the summary of that profiling run under profiles/,
+    which carries a line `traffic_bytes_per_launch[<workload>] = <bytes>`.  None when no such run is on file: the
+    timed run itself cannot read hardware counters."""
+    import re
+    path = os.path.join(ROOT, "profiles", "attn_fwd_hbm_traffic.md")
+    try:
+        text = open(path).read()
+    except OSError:
+        return None, None
+    m = re.search(r"traffic_bytes_per_launch\[%s\]\s*=\s*([0-9.eE+]+)" % re.escape(workload), text)
+    return (float(m.group(1)), "profiles/attn_fwd_hbm_traffic.md") if m else (None, None)
 
 
 def make_workload(name):
@@ -257,7 +269,13 @@ def main():
         del scratch, sigma
         if args.coverage and not given:
             # true attention mass inside the selected blocks (two more attention passes, untimed)
-            cov = pbs.coverage(p, Q, pipe.Kp, pipe.Vt, None, pipe.kidx, pipe.row_cnt, pipe.col_idx, ws=pipe.ws4)
+            _, lse_sel = pbs.attn_fwd(p, Q, pipe.Kp, pipe.Vt, None, pipe.kidx, pipe.row_cnt, pipe.col_idx, pipe.Op,
+                                      want_lse=True, ws=pipe.ws4)
+            rc_all, ci_all = pbs.admitted_lists(p)
+            _, lse_all = pbs.attn_fwd(p, Q, pipe.Kp, pipe.Vt, None, pipe.kidx, rc_all, ci_all, pipe.Op, want_lse=True,
+                                      ws=pipe.ws4)
+            cov = pbs.mass_covered(p, lse_sel, lse_all)
+            del rc_all, ci_all, lse_sel, lse_all
             extras["attention_mass_covered"] = {"mean": float(cov.mean()), "min_row": float(cov.min()),
                                                 "rows_below_tau": float((cov < w.tau).float().mean())}
             del cov
@@ -305,9 +323,29 @@ def main():
     }
     if given:
         alg_bytes = {"segment_permute": alg_bytes["segment_permute"] - w.batch * w.h_kv * w.n * 4}
-    if token_copy:                                     # K and V are read and written a second time, kidx written twice
-        alg_bytes["segment_permute"] += 2 * kv_bytes + w.batch * w.h_kv * w.n * 4
+    # bytes the permutation stage moves beyond the algorithmic ones: with the token-order copies K and V are read and
+    # written a second time (the second read mostly from cache) and a second index vector is written
+    moved_extra = {"segment_permute": 2 * kv_bytes + w.batch * w.h_kv * w.n * 4 if token_copy else 0}
     attn_tflops = flop / (stage_ms["attn_fwd"] * 1e-3) / 1e12
+    visited_tflops = visited * 4.0 * w.block * w.block * w.d / (stage_ms["attn_fwd"] * 1e-3) / 1e12
+    traffic, traffic_src = measured_attn_traffic(args.workload)
+    roofline = {"kernel": "pbs_attn_fwd", "bound": "mfma", "achieved": attn_tflops,
+                "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": attn_tflops / MFMA_BF16_PEAK_TFLOPS,
+                "frac_from_visited_blocks": visited_tflops / MFMA_BF16_PEAK_TFLOPS,
+                "traffic": traffic, "traffic_source": traffic_src or "not measured for this workload",
+                "avg_launch_ms": stage_ms["attn_fwd"]}
+    if given:
+        # Caller-supplied lists drawn independently per query head: no two heads of a group share K'/V'^T tiles, so
+        # every listed block fetches its 2 * block * d tile bytes (128 FLOP per byte), plus Q' and O' once.  Whichever
+        # bound is nearer names the line.
+        tile_bytes = visited * 2.0 * w.block * w.d * es + 2.0 * q_bytes
+        hbm_gbs = tile_bytes / (stage_ms["attn_fwd"] * 1e-3) / 1e9
+        roofline["frac_mfma"] = roofline["frac"]
+        roofline["frac_hbm_unshared_tiles"] = hbm_gbs / HBM_PEAK_GBS
+        if roofline["frac_hbm_unshared_tiles"] > roofline["frac_mfma"]:
+            roofline.update(bound="hbm", achieved=hbm_gbs, peak=HBM_PEAK_GBS, unit="GB/s",
+                            frac=hbm_gbs / HBM_PEAK_GBS)
+            roofline.pop("frac_from_visited_blocks")
     out = {
         "metric": "pbs_attn_prefill_effective_tflops", "value": flop / (ms_per_step * 1e-3) / 1e12, "unit": "TFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
@@ -320,9 +358,10 @@ def main():
                        permuted=not (given or args.no_permute)),
         "stages_ms": stage_ms,
         "stages_gbs": {k: alg_bytes[k] / (stage_ms[k] * 1e-3) / 1e9 for k in alg_bytes if stage_ms[k] > 0},
-        "roofline": {"kernel": "pbs_attn_fwd", "bound": "mfma", "achieved": attn_tflops,
-                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": attn_tflops / MFMA_BF16_PEAK_TFLOPS,
-                     "traffic": ATTN_TRAFFIC_BYTES.get(args.workload), "avg_launch_ms": stage_ms["attn_fwd"]},
+        "stages_frac_of_hbm_peak": {k: alg_bytes[k] / (stage_ms[k] * 1e-3) / 1e9 / HBM_PEAK_GBS
+                                    for k in alg_bytes if stage_ms[k] > 0},
+        "stages_algorithmic_bytes": alg_bytes, "stages_extra_bytes_moved": moved_extra,
+        "roofline": roofline,
         "context": {"paper_h100_128k_ms": {"flashattention": 443.29, "pbs_total": 159.87, "speedup": 2.77},
                     "input_generation_s": t_gen, **extras},
     }

@@ -73,8 +73,11 @@ typedef enum { PBS_F32 = 0, PBS_BF16 = 1 } pbs_dtype;
  *   other stage reads the first tensor as before, and pbs_attn_fwd may evaluate a query block's own segment from
  *   the second (see there).  The result is the same attention: the order in which keys are summed does not matter
  *   (Theorem 1).
+ * PBS_FLAG_RUNNING_MAX_ONLY: pbs_attn_fwd evaluates every query block with the running-maximum recurrence of
+ *   Algorithm 1 as printed (m moves and O, l are rescaled); for bf16, d = 128, block = 128 this leaves out the first
+ *   pass, which keeps a fixed softmax reference per query.  Same result up to rounding; slower.
  */
-enum { PBS_FLAG_FORCE_FIRST_BLOCK = 1u, PBS_FLAG_TOKEN_ORDER_COPY = 2u };
+enum { PBS_FLAG_FORCE_FIRST_BLOCK = 1u, PBS_FLAG_TOKEN_ORDER_COPY = 2u, PBS_FLAG_RUNNING_MAX_ONLY = 4u };
 
 typedef enum {
     PBS_STAGE_KEY_SCORES = 1,
@@ -160,7 +163,11 @@ pbs_status pbs_permute_rows(const pbs_problem *p, int32_t heads, const void *X, 
  *   a_i = softmax_j(Qbar_i . Kbar_j * scale) over the columns the extended causal mask C admits:
  *         j < (g(i)+1)*R for a query block inside full segment g(i), j <= i past the last full segment;
  *   stable descending sort (ties: lowest j), cumulative sum, k = min({t : c[t] >= tau} U {n_i}), first k kept.
- * All of this is IEEE fp64 so that the discrete result does not depend on the machine.  Then the blocks of the
+ * All of this is IEEE fp64 with separate multiplications and additions in the order of the definition (block means:
+ * rows ascending for fp32 storage; for bf16 storage any order gives the exact sum), so that the discrete result does
+ * not depend on how a machine rounds lower precision.  Two sums are formed in a tree order instead of left to right
+ * (the softmax denominator and the partial masses the threshold search compares with tau): a selection can differ
+ * from the left-to-right evaluation only if a cumulative mass lies within a few 1e-16 of tau.  Then the blocks of the
  * query block's own segment are switched on (Section "Effect of Segment Size": they cannot be skipped); past the
  * last full segment only the diagonal block; and block 0 when PBS_FLAG_FORCE_FIRST_BLOCK is set (Section
  * "Baselines").  Forced blocks do not change k.
@@ -187,8 +194,7 @@ pbs_status pbs_block_mask(const pbs_problem *p, const void *Qp, const void *Kp, 
  *   one that keeps a fixed softmax reference per query and writes one int32 flag per query block into ws (1 = some
  *   probability outgrew the reference by more than 2^64), and one that recomputes the flagged query blocks with the
  *   running-maximum recurrence of Algorithm 1.  The contents of ws need not be initialised and mean nothing afterwards.
- *   Setting the environment variable PBS_ATTN_NARROW (read once per process) sends every query block of that shape
- *   through the second kernel alone; it exists for A/B timing.
+ *   With PBS_FLAG_RUNNING_MAX_ONLY every query block of that shape goes through the second kernel alone.
  *   With PBS_FLAG_TOKEN_ORDER_COPY (Kp, Vt, kidx carry their token-order copies), qidx == NULL and that same shape, a
  *   query block inside a full segment whose list ends with all R blocks of its own segment, ascending (as
  *   pbs_block_mask writes them), takes these R blocks from the token-order copy instead: the blocks before the
@@ -205,6 +211,21 @@ pbs_status pbs_attn_fwd(const pbs_problem *p, const void *Qp, const void *Kp, co
  * partially overlap Op.
  */
 pbs_status pbs_unpermute(const pbs_problem *p, const void *Op, const int32_t *qidx, void *O, void *stream);
+
+/*
+ * Coverage tooling for the block-selection objective of Section "The Problem of Information Fragmentation" (the
+ * attention mass, softmax over every visible key, that falls into the selected blocks); not a step of Algorithm 1.
+ * pbs_admitted_lists writes the lists that name every key block the extended causal mask C admits (appendix "Block
+ * Selection in PBS-Attn"): row_cnt[b,h,i] = (g(i)+1)*R capped at T inside full segment g(i), i+1 past the last full
+ * segment; col_idx[b,h,i,0..row_cnt) = 0, 1, ...  (shapes as for pbs_block_mask; the rest of col_idx is untouched).
+ * pbs_mass_covered combines the log-sum-exp outputs of two pbs_attn_fwd calls, one over a selection and one over the
+ * admitted lists: covered[b,h,slot] = exp(lse_listed - lse_admitted), 0 where lse_listed is -inf.  All three
+ * [batch,h_q,n] float32; covered may alias either input.
+ * Errors: PBS_ERR_NULL, the statuses of pbs_validate, PBS_ERR_HIP.
+ */
+pbs_status pbs_admitted_lists(const pbs_problem *p, int32_t *row_cnt, int32_t *col_idx, void *stream);
+pbs_status pbs_mass_covered(const pbs_problem *p, const float *lse_listed, const float *lse_admitted, float *covered,
+                            void *stream);
 
 /*
  * Measurement aid, not a step of Algorithm 1: launches a kernel that does nothing but bf16 matrix instructions

@@ -6,9 +6,12 @@ and this module never imports the product package.
 
 All functions take numpy arrays.  Floating inputs are float32 arrays whose
 values are already rounded to the storage type (bf16 values are exactly
-representable in float32); the C code promotes them to double.  Each wrapper
-only marshals arguments; the arithmetic is in pbs_oracle.c, where every
-function cites the passage of the paper it follows.
+representable in float32); the C code promotes them to double.  The wrappers
+of the C functions only marshal arguments: that arithmetic is in pbs_oracle.c,
+where every function cites the passage of the paper it follows.  Three functions
+here are written in numpy instead and cite their passages themselves:
+all_allowed_lists (the columns the extended causal mask admits), coverage (two
+calls of the attention loop combined) and pipeline (the stages chained).
 """
 import ctypes
 import math

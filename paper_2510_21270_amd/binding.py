@@ -15,11 +15,12 @@ _lib = None
 
 PBS_F32, PBS_BF16 = 0, 1
 STAGE_KEY_SCORES, STAGE_SEGMENT_PERMUTE, STAGE_BLOCK_MASK, STAGE_ATTN_FWD, STAGE_UNPERMUTE = 1, 2, 3, 4, 5
-FLAG_FORCE_FIRST_BLOCK, FLAG_TOKEN_ORDER_COPY = 1, 2
+FLAG_FORCE_FIRST_BLOCK, FLAG_TOKEN_ORDER_COPY, FLAG_RUNNING_MAX_ONLY = 1, 2, 4
 
 EXPORTS = ["pbs_status_string", "pbs_validate", "pbs_workspace_bytes", "pbs_vt_bytes", "pbs_key_scores",
            "pbs_segment_permute", "pbs_permute_rows", "pbs_block_mask", "pbs_attn_fwd", "pbs_unpermute",
-           "pbs_mfma_rate_probe", "pbs_key_scores_static", "pbs_key_scores_static_scratch_bytes"]
+           "pbs_mfma_rate_probe", "pbs_key_scores_static", "pbs_key_scores_static_scratch_bytes", "pbs_admitted_lists",
+           "pbs_mass_covered"]
 
 
 class PbsError(RuntimeError):
@@ -37,7 +38,7 @@ def load_library():
     """Load libpbs.so built in-tree (python -m paper_2510_21270_amd.build).  Fails loudly when it is missing."""
     global _lib
     if _lib is None:
-        path = os.environ.get("PBS_LIBRARY", LIB_PATH)     # override for trying out another build of the library
+        path = LIB_PATH
         if not os.path.exists(path):
             raise PbsError("libpbs.so not found at %s: build it with `python -m paper_2510_21270_amd.build`" % path)
         lib = ctypes.CDLL(path)
@@ -58,6 +59,8 @@ def load_library():
         lib.pbs_block_mask.argtypes = [P, V, V, V, V, V, V, Z, V]
         lib.pbs_attn_fwd.argtypes = [P, V, V, V, V, V, V, V, V, V, V, Z, V]
         lib.pbs_unpermute.argtypes = [P, V, V, V, V]
+        lib.pbs_admitted_lists.argtypes = [P, V, V, V]
+        lib.pbs_mass_covered.argtypes = [P, V, V, V, V]
         lib.pbs_mfma_rate_probe.argtypes = [ctypes.c_int, ctypes.c_int, V, Z, ctypes.POINTER(ctypes.c_double), V]
         _lib = lib
     return _lib
@@ -225,28 +228,23 @@ def unpermute(p, Op, qidx, O=None):
     return O
 
 
-def all_allowed_lists(p, device="cuda"):
-    """row_cnt, col_idx naming every key block the extended causal mask admits (what a dense causal pass visits)."""
+def admitted_lists(p, row_cnt=None, col_idx=None, device="cuda"):
     T = T_of(p)
-    R, G = p.segment // p.block, p.n // p.segment
-    i = torch.arange(T, device=device)
-    s = i // R
-    allowed = torch.where(s < G, torch.clamp((s + 1) * R, max=T), i + 1).to(torch.int32)
-    row_cnt = allowed.view(1, 1, T).expand(p.batch, p.h_q, T).contiguous()
-    col_idx = torch.arange(T, device=device, dtype=torch.int32).view(1, 1, 1, T).expand(p.batch, p.h_q, T, T).contiguous()
+    if row_cnt is None:
+        row_cnt = torch.empty((p.batch, p.h_q, T), dtype=torch.int32, device=device)
+    if col_idx is None:
+        col_idx = torch.empty((p.batch, p.h_q, T, T), dtype=torch.int32, device=device)
+    _check(load_library().pbs_admitted_lists(ctypes.byref(p), _ptr(row_cnt), _ptr(col_idx), _stream()),
+           "pbs_admitted_lists")
     return row_cnt, col_idx
 
 
-def coverage(p, Qp, Kp, Vt, qidx, kidx, row_cnt, col_idx, ws=None):
-    """Attention mass that the listed blocks capture, per query slot [batch, h_q, n] (float32): the inner sums of the
-    block-selection objective in Section "The Problem of Information Fragmentation", A being the softmax over every
-    visible key.  Two pbs_attn_fwd calls: exp(lse over the listed blocks - lse over all admitted blocks)."""
-    Op = torch.empty_like(Qp)
-    _, lse_sel = attn_fwd(p, Qp, Kp, Vt, qidx, kidx, row_cnt, col_idx, Op, want_lse=True, ws=ws)
-    rc_all, ci_all = all_allowed_lists(p, Qp.device)
-    _, lse_all = attn_fwd(p, Qp, Kp, Vt, qidx, kidx, rc_all, ci_all, Op, want_lse=True, ws=ws)
-    cov = torch.exp(lse_sel - lse_all)
-    return torch.where(torch.isfinite(lse_sel), cov, torch.zeros_like(cov))
+def mass_covered(p, lse_listed, lse_admitted, covered=None):
+    if covered is None:
+        covered = torch.empty_like(lse_listed)
+    _check(load_library().pbs_mass_covered(ctypes.byref(p), _ptr(lse_listed), _ptr(lse_admitted), _ptr(covered),
+                                           _stream()), "pbs_mass_covered")
+    return covered
 
 
 def mfma_rate_probe(random_operands, iters=20000, reps=3):

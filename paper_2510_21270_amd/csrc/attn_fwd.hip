@@ -16,7 +16,6 @@
 //
 // Vector kernel (fp32 arithmetic): every other supported dtype / d / block.
 #include <limits.h>
-#include <stdlib.h>
 
 #include "pbs_host.h"
 
@@ -571,9 +570,8 @@ static pbs_status launch_vector(const Geo &g, const void *Qp, const void *Kp, co
                                               160 * 1024 - 2048, lds_raised);
         if (st != PBS_OK) return st;
     }
-    hipLaunchKernelGGL((attn_vector_kernel<E, D>), dim3(g.T, g.batch * g.h_q), dim3(2 * g.block), lds, s,
+    return launch((attn_vector_kernel<E, D>), dim3(g.T, g.batch * g.h_q), dim3(2 * g.block), lds, s,
                        (const E *)Qp, (const E *)Kp, (const E *)Vt, qidx, kidx, row_cnt, col_idx, (E *)Op, lse, g);
-    return launch_status();
 }
 
 }  // namespace pbs
@@ -595,7 +593,7 @@ extern "C" pbs_status pbs_attn_fwd(const pbs_problem *p, const void *Qp, const v
     if (p->dtype == PBS_BF16 && p->d == 128 && (p->block == 128 || p->block == 64)) {
         const int ncoh = g.batch * g.h_kv * ((g.r * g.T + kCohort - 1) / kCohort);
         const dim3 mgrid((unsigned)(((ncoh + kXcds - 1) / kXcds) * kCohort * kXcds));
-        static const bool narrow_only = getenv("PBS_ATTN_NARROW") != nullptr;
+        const bool narrow_only = (p->flags & PBS_FLAG_RUNNING_MAX_ONLY) != 0;
         if (p->block == 128) {
             // first pass: every query block with a fixed softmax reference; second pass: the flagged blocks (none
             // on ordinary inputs, then each workgroup of the second launch leaves at once) with the rescaling kernel
@@ -610,15 +608,15 @@ extern "C" pbs_status pbs_attn_fwd(const pbs_problem *p, const void *Qp, const v
                 st = launch_attn_wide(g, Qp, Kp, Vt, qidx, kidx, row_cnt, col_idx, Op, lse, redo, tok_delta, s);
                 if (st != PBS_OK) return st;
             }
-            hipLaunchKernelGGL((attn_mfma_kernel<128, 4, 64>), mgrid, dim3(256), 0, s, (const bf16_t *)Qp,
+            st = launch((attn_mfma_kernel<128, 4, 64>), mgrid, dim3(256), 0, s, (const bf16_t *)Qp,
                                (const bf16_t *)Kp, (const bf16_t *)Vt, qidx, kidx, row_cnt, col_idx, (bf16_t *)Op, lse,
                                (const int32_t *)redo, g);
         } else {
-            hipLaunchKernelGGL((attn_mfma_kernel<64, 2, 32>), mgrid, dim3(128), 0, s, (const bf16_t *)Qp,
+            st = launch((attn_mfma_kernel<64, 2, 32>), mgrid, dim3(128), 0, s, (const bf16_t *)Qp,
                                (const bf16_t *)Kp, (const bf16_t *)Vt, qidx, kidx, row_cnt, col_idx, (bf16_t *)Op, lse,
                                (const int32_t *)nullptr, g);
         }
-        return launch_status();
+        return st;
     }
     if (p->dtype == PBS_BF16)
         return p->d == 128 ? launch_vector<bf16_t, 128>(g, Qp, Kp, Vt, qidx, kidx, row_cnt, col_idx, Op, lse, s)
@@ -626,3 +624,4 @@ extern "C" pbs_status pbs_attn_fwd(const pbs_problem *p, const void *Qp, const v
     return p->d == 128 ? launch_vector<float, 128>(g, Qp, Kp, Vt, qidx, kidx, row_cnt, col_idx, Op, lse, s)
                        : launch_vector<float, 64>(g, Qp, Kp, Vt, qidx, kidx, row_cnt, col_idx, Op, lse, s);
 }
+

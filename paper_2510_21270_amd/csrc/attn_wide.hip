@@ -608,9 +608,8 @@ pbs_status launch_attn_wide(const Geo &g, const void *Qp, const void *Kp, const 
 {
     const int ncoh = g.batch * g.h_kv * ((g.r * g.T + wide::kCohort - 1) / wide::kCohort);
     const dim3 grid((unsigned)(((ncoh + wide::kXcds - 1) / wide::kXcds) * wide::kCohort * wide::kXcds));
-    hipLaunchKernelGGL(wide::attn_wide_kernel, grid, dim3(128), 0, s, (const bf16_t *)Qp, (const bf16_t *)Kp,
+    return launch(wide::attn_wide_kernel, grid, dim3(128), 0, s, (const bf16_t *)Qp, (const bf16_t *)Kp,
                        (const bf16_t *)Vt, qidx, kidx, row_cnt, col_idx, (bf16_t *)Op, lse, redo, g, tok_delta);
-    return launch_status();
 }
 
 }  // namespace pbs

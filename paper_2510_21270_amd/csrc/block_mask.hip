@@ -2,8 +2,12 @@
 //
 // Everything that decides the discrete result runs in IEEE fp64 with the plain operation order (no fused
 // multiply-add in the logits), so the mask does not depend on how a machine rounds lower precision:
-//   1. pool_kernel     block means of K' (HBM-bound; sums of bf16 values are exact in fp64), stored d-major
-//                      ([head][e][T]) so that the next kernel reads them coalesced.
+//   1. pool_kernel     block means of K' (HBM-bound), stored d-major ([head][e][T]) so that the next kernel reads
+//                      them coalesced.  A sum of up to 128 bf16 values is exact in fp64 in any order (8 significant
+//                      bits each; the exponents of one column would have to spread over more than 38 binades to lose
+//                      a bit), so bf16 inputs are summed in whatever order loads best.  fp32 values have 24 significant
+//                      bits and no such slack: they are added one row after the other, in ascending order, which
+//                      is the order of the plain definition.
 //   2. select_kernel   block means of its own Q' blocks, then logits of up to four query heads of one group against
 //                      the allowed columns, softmax, the mass threshold by bisection (one wave per row), forced
 //                      blocks, then bit-mask words by wave ballot and the ascending column list by prefix popcount.
@@ -28,11 +32,22 @@ __global__ __launch_bounds__(256) void pool_kernel(const E *__restrict__ X, doub
     const int RG = 256 / cpr;
     const int cg = threadIdx.x % cpr, rg = threadIdx.x / cpr;
     const int lo = i * block, hi = min(n, lo + block);
+    if constexpr (sizeof(E) == 4) {
+        // fp32 storage: thread e owns column e and adds its rows in ascending order
+        if ((int)threadIdx.x < d) {
+            const int e = threadIdx.x;
+            double s = 0.0;
+            for (int row = lo; row < hi; ++row) s += (double)ElemTraits<E>::to_float(X[(head * n + row) * (size_t)d + e]);
+            const double mean = s / (double)(hi - lo);
+            if (TRANSPOSED) out[(head * d + e) * (size_t)T + i] = mean;
+            else out[(head * T + i) * (size_t)d + e] = mean;
+        }
+        return;
+    }
     double acc[VEC];
 #pragma unroll
     for (int u = 0; u < VEC; ++u) acc[u] = 0.0;
-    // four independent 16-byte loads in flight per thread; rows are added in ascending order as before (the sums
-    // are exact in fp64 whatever the order)
+    // four independent 16-byte loads in flight per thread (bf16: the sums are exact in fp64 whatever the order)
     constexpr int U = 4;
     for (int row = lo + rg; row < hi; row += U * RG) {
         vec_t v[U];
@@ -116,7 +131,19 @@ __global__ __launch_bounds__(64 * RB) void select_kernel(const E *__restrict__ Q
     // Block mean of query block i of row w, by wave w (sums of storage values in fp64; 16-byte column groups, four
     // loads in flight per lane, then the row groups of the wave are added up).  Pooling Q' here instead of in a
     // kernel of its own lets the 1 GiB read of Q' overlap with the arithmetic of other workgroups.
-    {
+    // fp32 storage: every lane owns columns and adds their rows in ascending order (see the note at the top).
+    if constexpr (sizeof(E) == 4) {
+        const int w = tid >> 6, lane = tid & 63;
+        const int lo = i * g.block, hi = min(g.n, lo + g.block);
+        if (w < rows) {
+            const E *X = Qp + (size_t)(bhq0 + w) * g.n * g.d;
+            for (int e = lane; e < g.d; e += 64) {
+                double s = 0.0;
+                for (int row = lo; row < hi; ++row) s += (double)ElemTraits<E>::to_float(X[(size_t)row * g.d + e]);
+                qs[w][e] = s / (double)(hi - lo);
+            }
+        }
+    } else {
         constexpr int VEC = 16 / sizeof(E);
         typedef E vec_t __attribute__((ext_vector_type(VEC)));
         const int w = tid >> 6, lane = tid & 63;
@@ -279,9 +306,8 @@ static pbs_status launch_select(const E *Qp, const double *KbarT, uint64_t *mask
                                               RB * kMaxT * (int)sizeof(double), lds_raised);
         if (st != PBS_OK) return st;
     }
-    hipLaunchKernelGGL((select_kernel<RB, E>), dim3(g.T, g.batch * g.h_kv * chunks), dim3(64 * RB), lds, s, Qp, KbarT,
+    return launch((select_kernel<RB, E>), dim3(g.T, g.batch * g.h_kv * chunks), dim3(64 * RB), lds, s, Qp, KbarT,
                        mask_bits, row_cnt, col_idx, g, chunks, Tpad);
-    return launch_status();
 }
 
 size_t ws_block_mask(const pbs_problem *p)
@@ -307,17 +333,15 @@ extern "C" pbs_status pbs_block_mask(const pbs_problem *p, const void *Qp, const
     double *KbarT = reinterpret_cast<double *>(ws);
     const int nk = g.batch * g.h_kv;
     if (p->dtype == PBS_BF16) {
-        hipLaunchKernelGGL((pool_kernel<bf16_t, true>), dim3(g.T, nk), dim3(256), 0, s, (const bf16_t *)Kp, KbarT, g.n,
-                           g.d, g.block, g.T);
-        if ((st = launch_status()) != PBS_OK) return st;
+        if ((st = launch((pool_kernel<bf16_t, true>), dim3(g.T, nk), dim3(256), 0, s, (const bf16_t *)Kp, KbarT, g.n,
+                           g.d, g.block, g.T)) != PBS_OK) return st;
         const bf16_t *Q = (const bf16_t *)Qp;
         if (g.r >= 3) return launch_select<4>(Q, KbarT, mask_bits, row_cnt, col_idx, g, s);
         if (g.r == 2) return launch_select<2>(Q, KbarT, mask_bits, row_cnt, col_idx, g, s);
         return launch_select<1>(Q, KbarT, mask_bits, row_cnt, col_idx, g, s);
     }
-    hipLaunchKernelGGL((pool_kernel<float, true>), dim3(g.T, nk), dim3(256), 0, s, (const float *)Kp, KbarT, g.n, g.d,
-                       g.block, g.T);
-    if ((st = launch_status()) != PBS_OK) return st;
+    if ((st = launch((pool_kernel<float, true>), dim3(g.T, nk), dim3(256), 0, s, (const float *)Kp, KbarT, g.n, g.d,
+                       g.block, g.T)) != PBS_OK) return st;
     const float *Q = (const float *)Qp;
     if (g.r >= 3) return launch_select<4>(Q, KbarT, mask_bits, row_cnt, col_idx, g, s);
     if (g.r == 2) return launch_select<2>(Q, KbarT, mask_bits, row_cnt, col_idx, g, s);

@@ -414,17 +414,14 @@ static pbs_status run_generic(const pbs_problem *p, const Geo &g, const void *Q,
     ws += align_up((size_t)nbh * bl * chunks * sizeof(double2), kWsAlign);
     double2 *stats = reinterpret_cast<double2 *>(ws);
     pbs_status st;
-    hipLaunchKernelGGL(qhat_f64_kernel<E>, dim3(nbh), dim3(256), 0, s, (const E *)Q, qhat, g, bl);
-    if ((st = launch_status()) != PBS_OK) return st;
-    hipLaunchKernelGGL(scores_stats_f64_kernel<E>, dim3(chunks, bl, nbh), dim3(256), 0, s, (const E *)K, qhat, partial,
-                       g, bl, kGenericKeysPerChunk);
-    if ((st = launch_status()) != PBS_OK) return st;
-    hipLaunchKernelGGL(scores_merge_f64_kernel, dim3(nbh), dim3(128), 0, s, partial, stats, bl, chunks);
-    if ((st = launch_status()) != PBS_OK) return st;
-    hipLaunchKernelGGL(scores_final_f64_kernel<E>, dim3(ceil_div(g.n, 256), nbh), dim3(256), 0, s, (const E *)K, qhat,
+    if ((st = launch(qhat_f64_kernel<E>, dim3(nbh), dim3(256), 0, s, (const E *)Q, qhat, g, bl)) != PBS_OK) return st;
+    if ((st = launch(scores_stats_f64_kernel<E>, dim3(chunks, bl, nbh), dim3(256), 0, s, (const E *)K, qhat, partial,
+                       g, bl, kGenericKeysPerChunk)) != PBS_OK) return st;
+    if ((st = launch(scores_merge_f64_kernel, dim3(nbh), dim3(128), 0, s, partial, stats, bl, chunks)) != PBS_OK) return st;
+    st = launch(scores_final_f64_kernel<E>, dim3(ceil_div(g.n, 256), nbh), dim3(256), 0, s, (const E *)K, qhat,
                        stats, scores, g, bl);
     (void)p;
-    return launch_status();
+    return st;
 }
 
 }  // namespace pbs
@@ -451,15 +448,11 @@ static pbs_status enqueue_key_scores(const pbs_problem *p, const void *Q, const 
     float2 *partial = reinterpret_cast<float2 *>(w);
     w += align_up((size_t)nbh * nwg * kQRows * sizeof(float2), kWsAlign);
     float *cvec = reinterpret_cast<float *>(w);
-    hipLaunchKernelGGL(qhat_split_kernel, dim3(kQRows / 8, nbh), dim3(256), 0, s, (const bf16_t *)Q, qsplit, g, bl);
-    if ((st = launch_status()) != PBS_OK) return st;
-    hipLaunchKernelGGL(scores_sweep1_kernel, dim3(nwg, nbh), dim3(256), 0, s, (const bf16_t *)K, qsplit, partial, g, kpw);
-    if ((st = launch_status()) != PBS_OK) return st;
-    hipLaunchKernelGGL(scores_merge_kernel, dim3(nbh), dim3(1024), 0, s, partial, cvec, nwg, bl);
-    if ((st = launch_status()) != PBS_OK) return st;
-    hipLaunchKernelGGL(scores_sweep2_kernel, dim3(nwg, nbh), dim3(256), 0, s, (const bf16_t *)K, qsplit, cvec, scores,
+    if ((st = launch(qhat_split_kernel, dim3(kQRows / 8, nbh), dim3(256), 0, s, (const bf16_t *)Q, qsplit, g, bl)) != PBS_OK) return st;
+    if ((st = launch(scores_sweep1_kernel, dim3(nwg, nbh), dim3(256), 0, s, (const bf16_t *)K, qsplit, partial, g, kpw)) != PBS_OK) return st;
+    if ((st = launch(scores_merge_kernel, dim3(nbh), dim3(1024), 0, s, partial, cvec, nwg, bl)) != PBS_OK) return st;
+    return launch(scores_sweep2_kernel, dim3(nwg, nbh), dim3(256), 0, s, (const bf16_t *)K, qsplit, cvec, scores,
                        g, kpw);
-    return launch_status();
 }
 
 extern "C" pbs_status pbs_key_scores(const pbs_problem *p, const void *Q, const void *K, float *scores, void *ws,

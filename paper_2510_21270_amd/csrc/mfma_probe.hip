@@ -58,8 +58,8 @@ extern "C" pbs_status pbs_mfma_rate_probe(int random_operands, int iters, float 
     using namespace pbs;
     if (!sink || !flop) return PBS_ERR_NULL;
     if (iters < 1 || iters > (1 << 22) || sink_floats < (size_t)kProbeGroups * kProbeThreads) return PBS_ERR_SHAPE;
-    hipLaunchKernelGGL(mfma_probe_kernel, dim3(kProbeGroups), dim3(kProbeThreads), 0, (hipStream_t)stream, sink, iters,
+    const pbs_status st = launch(mfma_probe_kernel, dim3(kProbeGroups), dim3(kProbeThreads), 0, (hipStream_t)stream, sink, iters,
                        random_operands);
     *flop = (double)kProbeGroups * (kProbeThreads / kWave) * (double)iters * kProbeMfmas * (2.0 * 32 * 32 * 16);
-    return launch_status();
+    return st;
 }

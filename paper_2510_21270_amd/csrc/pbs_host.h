@@ -3,6 +3,8 @@
 #include <math.h>
 
 #include <atomic>
+#include <tuple>
+#include <type_traits>
 
 #include "pbs_device.h"
 
@@ -59,9 +61,21 @@ inline pbs_status check_ws(const pbs_problem *p, int stage, const void *ws, size
     return PBS_OK;
 }
 
-inline pbs_status launch_status()
+// Enqueues `kernel` and returns the status of this very launch (the return value of hipLaunchKernel), so that an
+// error left behind by some earlier, unrelated runtime call is neither reported as ours nor cleared.  The arguments
+// are converted to the kernel's parameter types first.
+template <typename... Params, typename... Args>
+inline pbs_status launch(void (*kernel)(Params...), dim3 grid, dim3 block, size_t lds, hipStream_t s, Args &&...args)
 {
-    return hipGetLastError() == hipSuccess ? PBS_OK : PBS_ERR_HIP;
+    static_assert(sizeof...(Params) == sizeof...(Args), "one argument per kernel parameter");
+    std::tuple<typename std::remove_cv<Params>::type...> vals{static_cast<Params>(args)...};
+    return std::apply(
+        [&](auto &...v) {
+            void *ptrs[] = {static_cast<void *>(&v)...};
+            return hipLaunchKernel(reinterpret_cast<const void *>(kernel), grid, block, ptrs, lds, s) == hipSuccess
+                       ? PBS_OK : PBS_ERR_HIP;
+        },
+        vals);
 }
 
 // Raises a kernel's dynamic LDS limit once per device (the attribute belongs to the current device's copy of the

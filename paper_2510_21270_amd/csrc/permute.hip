@@ -261,35 +261,34 @@ extern "C" pbs_status pbs_segment_permute(const pbs_problem *p, const float *sco
         int p2 = 1;
         while (p2 < g.segment) p2 <<= 1;
         const int threads = p2 / 2 < 64 ? 64 : (p2 / 2 > 1024 ? 1024 : p2 / 2);
-        hipLaunchKernelGGL(segment_argsort_kernel, dim3(g.G + 1, nbh), dim3(threads), (size_t)p2 * sizeof(uint64_t), s,
+        st = launch(segment_argsort_kernel, dim3(g.G + 1, nbh), dim3(threads), (size_t)p2 * sizeof(uint64_t), s,
                            scores, kidx, kidx_tok, g.n, g.segment, g.G, p2);
     } else {
         const size_t total = (size_t)nbh * g.n;
-        hipLaunchKernelGGL(iota_kernel, dim3(grid_for(total, 256)), dim3(256), 0, s, kidx, kidx_tok, g.n, total);
+        st = launch(iota_kernel, dim3(grid_for(total, 256)), dim3(256), 0, s, kidx, kidx_tok, g.n, total);
     }
-    if ((st = launch_status()) != PBS_OK) return st;
+    if (st != PBS_OK) return st;
     if (!Kp) return PBS_OK;
     const size_t es = elem_size(p->dtype);
     const int cpr = (int)(g.d * es / 16);
     const size_t vt_half = (size_t)nbh * g.T * g.d * g.block;           // elements
     dim3 mg = move_grid(g.n, cpr, nbh);
     if (token_copy) mg.x *= 2;
-    hipLaunchKernelGGL(move_rows_kernel<false>, mg, dim3(256), 0, s, (const uintx4 *)K, (const int32_t *)kidx,
-                       (uintx4 *)Kp, g.n, ilog2(cpr), token_copy ? tok_rows * cpr : (size_t)0);
-    if ((st = launch_status()) != PBS_OK) return st;
+    if ((st = launch(move_rows_kernel<false>, mg, dim3(256), 0, s, (const uintx4 *)K, (const int32_t *)kidx,
+                       (uintx4 *)Kp, g.n, ilog2(cpr), token_copy ? tok_rows * cpr : (size_t)0)) != PBS_OK) return st;
     const dim3 vg(token_copy ? 2 * g.T : g.T, nbh);
     if (p->dtype == PBS_BF16) {
         const size_t lds = (size_t)g.block * g.d * 2 + (size_t)(g.block / 8) * (64 / (vt_group(g.block) / 8)) * 4;   // tile + skew
-        hipLaunchKernelGGL(gather_vt_kernel<uint16_t>, vg, dim3(256), lds, s, (const uint16_t *)V,
+        st = launch(gather_vt_kernel<uint16_t>, vg, dim3(256), lds, s, (const uint16_t *)V,
                            (const int32_t *)kidx, (uint16_t *)Vt, g.n, g.d, g.block, g.T,
                            token_copy ? vt_half : (size_t)0);
     } else {
         const size_t lds = (size_t)g.block * g.d * 4 + (size_t)(g.block / 4) * (64 / (vt_group(g.block) / 4)) * 4;
-        hipLaunchKernelGGL(gather_vt_kernel<uint32_t>, vg, dim3(256), lds, s, (const uint32_t *)V,
+        st = launch(gather_vt_kernel<uint32_t>, vg, dim3(256), lds, s, (const uint32_t *)V,
                            (const int32_t *)kidx, (uint32_t *)Vt, g.n, g.d, g.block, g.T,
                            token_copy ? vt_half : (size_t)0);
     }
-    return launch_status();
+    return st;
 }
 
 extern "C" pbs_status pbs_permute_rows(const pbs_problem *p, int32_t heads, const void *X, const int32_t *idx,
@@ -299,11 +298,11 @@ extern "C" pbs_status pbs_permute_rows(const pbs_problem *p, int32_t heads, cons
     if (st != PBS_OK) return st;
     if (!X || !idx || !Xp) return PBS_ERR_NULL;
     if (heads < 1) return PBS_ERR_SHAPE;
+    if ((long long)p->batch * heads > 65535) return PBS_ERR_UNSUPPORTED;   // heads ride on gridDim.y
     if (!aligned16(X) || !aligned16(Xp) || X == Xp) return PBS_ERR_SHAPE;
     const int cpr = (int)(p->d * elem_size(p->dtype) / 16);
-    hipLaunchKernelGGL(move_rows_kernel<false>, move_grid(p->n, cpr, p->batch * heads), dim3(256), 0,
+    return launch(move_rows_kernel<false>, move_grid(p->n, cpr, p->batch * heads), dim3(256), 0,
                        (hipStream_t)stream, (const uintx4 *)X, idx, (uintx4 *)Xp, p->n, ilog2(cpr), (size_t)0);
-    return launch_status();
 }
 
 extern "C" pbs_status pbs_unpermute(const pbs_problem *p, const void *Op, const int32_t *qidx, void *O, void *stream)
@@ -314,7 +313,6 @@ extern "C" pbs_status pbs_unpermute(const pbs_problem *p, const void *Op, const 
     if (!aligned16(Op) || !aligned16(O)) return PBS_ERR_SHAPE;
     if (Op == O) return qidx ? PBS_ERR_SHAPE : PBS_OK;     // in place only for the identity
     const int cpr = (int)(p->d * elem_size(p->dtype) / 16);
-    hipLaunchKernelGGL(move_rows_kernel<true>, move_grid(p->n, cpr, p->batch * p->h_q), dim3(256), 0,
+    return launch(move_rows_kernel<true>, move_grid(p->n, cpr, p->batch * p->h_q), dim3(256), 0,
                        (hipStream_t)stream, (const uintx4 *)Op, qidx, (uintx4 *)O, p->n, ilog2(cpr), (size_t)0);
-    return launch_status();
 }

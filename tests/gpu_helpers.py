@@ -65,3 +65,13 @@ def with_token_copy(p, kind, first, second):
     x.copy_(first)
     pbs.token_copy(p, x, 1 if kind == "kidx" else p.d).copy_(second)
     return x
+
+
+def coverage(p, Qp, Kp, Vt, qidx, kidx, row_cnt, col_idx):
+    """Attention mass inside the listed blocks [batch, h_q, n]: two pbs_attn_fwd calls (the listed blocks, every
+    admitted block) and the two coverage entry points of the library."""
+    Op = torch.empty_like(Qp)
+    _, lse_sel = pbs.attn_fwd(p, Qp, Kp, Vt, qidx, kidx, row_cnt, col_idx, Op, want_lse=True)
+    rc_all, ci_all = pbs.admitted_lists(p)
+    _, lse_all = pbs.attn_fwd(p, Qp, Kp, Vt, qidx, kidx, rc_all, ci_all, Op, want_lse=True)
+    return pbs.mass_covered(p, lse_sel, lse_all), rc_all, ci_all

@@ -111,7 +111,7 @@ def test_full_size_attention_on_sampled_rows(oracle, name):
     check_close(to_host(Op2[0, 0]), to_host(Op[0, 0]), "bf16", "%s head 0, copy against permuted order" % name)
 
 
-@pytest.mark.parametrize("rho", [0.10, 1.0])
+@pytest.mark.parametrize("rho", [0.05, 0.10, 0.25, 0.50, 1.0])
 def test_full_size_given_lists_on_sampled_rows(oracle, rho):
     """Config 5: identity key order, seeded block lists of density rho at N = 65536, attention only."""
     _state.clear()
@@ -137,10 +137,42 @@ def test_full_size_given_lists_on_sampled_rows(oracle, rho):
     assert torch.isfinite(Op).all()
 
 
-def test_maximum_length_dense_equals_causal_attention_on_sampled_blocks():
+def test_block_64_at_full_length_on_sampled_rows(oracle):
+    """The block-64 matrix-core instantiation at N = 32768 (T = 512, segments of 8 blocks, GQA 4:1): every stage fed
+    the oracle's previous stage; indices, mask and lists in full and bit-exact, attention on sampled query blocks."""
+    _state.clear()
+    torch.cuda.empty_cache()
+    w = wl.planted("b64_full", 1064, 8, 2, 32768, 128, 64, 512, 0.9, "bf16", 64, rope_base=5e5)
+    s_h = oracle.key_scores(w.Q, w.K, w.block).astype(np.float32)
+    kidx = oracle.segment_argsort(s_h, w.segment)
+    Kp, Vp = oracle.gather_rows(w.K, kidx), oracle.gather_rows(w.V, kidx)
+    mask, row_cnt, col_idx = oracle.block_mask(w.Q, Kp, w.block, w.segment, w.tau, flags=w.flags)
+    p = make_problem(w)
+    Q, K, V = to_dev(w.Q, "bf16"), to_dev(w.K, "bf16"), to_dev(w.V, "bf16")
+    kidx_g, Kp_g, Vt_g = pbs.segment_permute(p, torch.from_numpy(s_h).cuda(), K, V)
+    assert np.array_equal(kidx_g.cpu().numpy(), kidx)
+    assert torch.equal(Kp_g, to_dev(Kp, "bf16")) and torch.equal(Vt_g, to_dev(vt_layout(Vp, w.block), "bf16"))
+    bits, cnt, cols = pbs.block_mask(p, Q, Kp_g)
+    assert np.array_equal(mask_from_bits(bits, w.T), mask) and np.array_equal(cnt.cpu().numpy(), row_cnt)
+    Op, lse = pbs.attn_fwd(p, Q, Kp_g, Vt_g, None, kidx_g, i32_dev(row_cnt), i32_dev(col_idx), want_lse=True)
+    torch.cuda.synchronize()
+    T, R = w.T, w.segment // w.block
+    rng = np.random.default_rng(6)
+    rows = [[0, int(rng.integers(0, w.h_q)), int(i)]
+            for i in [0, 1, R - 1, R, T // 2, T - R, T - 2, T - 1] + rng.integers(0, T, size=6).tolist()]
+    want, want_lse = oracle.attn_rows(w.Q, Kp, Vp, None, kidx, row_cnt, col_idx, w.block, rows, want_lse=True)
+    for u, (b, h, i) in enumerate(rows):
+        sl = slice(i * w.block, (i + 1) * w.block)
+        check_close(to_host(Op[b, h, sl]), want[u], "bf16", "block 64 row (%d,%d,%d)" % (b, h, i))
+        np.testing.assert_allclose(lse[b, h, sl].cpu().numpy(), want_lse[u], rtol=0, atol=2e-2)
+    assert torch.isfinite(Op).all()
+
+
+def test_maximum_length_dense_equals_causal_attention_on_sampled_blocks(oracle):
     # the largest supported length (T = 4096 blocks): tau > 1 keeps every admitted block, so whatever the scores made
     # of the key order, the pipeline must reproduce dense causal attention (Theorem 1).  Sampled query blocks are
-    # compared with fp32 matrix products of the very same bf16 inputs; no oracle run fits this size.
+    # compared with the oracle's attention loop fed the GPU's own permutation and lists, and with fp32 matrix
+    # products of the very same bf16 inputs in token order.
     N, Hq, Hkv, d, B, S = 524288, 4, 1, 128, 128, 1024
     gen = torch.Generator(device="cuda").manual_seed(11)
     Q = torch.randn(1, Hq, N, d, device="cuda", generator=gen).to(torch.bfloat16)
@@ -154,7 +186,21 @@ def test_maximum_length_dense_equals_causal_attention_on_sampled_blocks():
     assert int(pipe.row_cnt.sum()) == Hq * (S // B) ** 2 * (N // S) * (N // S + 1) // 2     # R^2 G (G + 1) / 2 per head
     seg = torch.arange(N, device="cuda") // S
     assert torch.equal(pipe.kidx[0, 0].long() // S, seg)                  # every key stays in its segment
-    for (h, i) in [(0, 0), (1, 1), (2, T // 2 + 3), (3, T - 1), (0, T - 8)]:
+    picks = [(0, 0), (1, 1), (2, T // 2 + 3), (3, T - 1), (0, T - 8)]
+    # oracle.attn_rows on these five query blocks: same inputs, the GPU's kidx and lists (only these rows are filled in)
+    Qh, Kh, Vh = Q.float().cpu().numpy(), K.float().cpu().numpy(), V.float().cpu().numpy()
+    kg = pipe.kidx.cpu().numpy()
+    rc_h = np.zeros((1, Hq, T), dtype=np.int32)
+    ci_h = np.zeros((1, Hq, T, T), dtype=np.int32)
+    for (h, i) in picks:
+        rc_h[0, h, i] = int(pipe.row_cnt[0, h, i])
+        ci_h[0, h, i] = pipe.col_idx[0, h, i].cpu().numpy()
+    want = oracle.attn_rows(Qh, oracle.gather_rows(Kh, kg), oracle.gather_rows(Vh, kg), None, kg, rc_h, ci_h, B,
+                            [[0, h, i] for (h, i) in picks])
+    for u, (h, i) in enumerate(picks):
+        check_close(to_host(O[0, h, i * B:(i + 1) * B]), want[u], "bf16", "N = 524288 block (%d,%d)" % (h, i))
+    del Qh, Kh, Vh, ci_h
+    for (h, i) in picks:
         q = Q[0, h, i * B:(i + 1) * B].float()
         k = K[0, 0, :(i + 1) * B].float()
         v = V[0, 0, :(i + 1) * B].float()

@@ -12,7 +12,7 @@ import numpy as np
 import pytest
 import torch
 
-from gpu_helpers import (check_close, i32_dev, make_problem, mask_from_bits, to_dev, to_host, vt_layout)
+from gpu_helpers import (check_close, coverage, i32_dev, make_problem, mask_from_bits, to_dev, to_host, vt_layout)
 from paper_2510_21270_amd import binding as pbs
 from paper_2510_21270_amd import workloads as wl
 
@@ -143,10 +143,15 @@ def test_coverage_of_the_selected_blocks(lib, oracle, name, sigma):
     w, res = _oracle_run(oracle, name, sigma)
     p = make_problem(w)
     qidx = i32_dev(res["qidx"]) if sigma else None
-    got = pbs.coverage(p, to_dev(res["Qp"], w.dtype), to_dev(res["Kp"], w.dtype),
-                       to_dev(vt_layout(res["Vp"], w.block), w.dtype), qidx, i32_dev(res["kidx"]),
-                       i32_dev(res["row_cnt"]), i32_dev(res["col_idx"]))
+    got, rc_all, ci_all = coverage(p, to_dev(res["Qp"], w.dtype), to_dev(res["Kp"], w.dtype),
+                                   to_dev(vt_layout(res["Vp"], w.block), w.dtype), qidx, i32_dev(res["kidx"]),
+                                   i32_dev(res["row_cnt"]), i32_dev(res["col_idx"]))
     torch.cuda.synchronize()
+    # the admitted lists are pure geometry: bit-exact against the oracle's
+    rc_want, ci_want = oracle.all_allowed_lists(w.batch, w.h_q, w.n, w.block, w.segment)
+    assert np.array_equal(rc_all.cpu().numpy(), rc_want)
+    listed = np.arange(w.T)[None, None, None, :] < rc_want[..., None]
+    assert np.array_equal(np.where(listed, ci_all.cpu().numpy(), -1), np.where(listed, ci_want, -1))
     want = oracle.coverage(res["Qp"], res["Kp"], res["qidx"], res["kidx"], res["row_cnt"], res["col_idx"], w.block,
                            w.segment)
     got = got.cpu().numpy()
