@@ -201,9 +201,10 @@ def main():
         else:
             pbs.key_scores(p, Q, K, pipe.scores, pipe.ws1)
             mark(1)
-            pbs.segment_permute(p, None if args.no_permute else pipe.scores, K, V, pipe.kidx, pipe.Kp, pipe.Vt)
+            pbs.segment_permute(p, None if args.no_permute else pipe.scores, K, V, pipe.kidx, pipe.Kp, pipe.Vt,
+                                ws=pipe.ws3)          # the block means of K' come out of the gather
             mark(2)
-            pbs.block_mask(p, Q, pipe.Kp, pipe.mask_bits, pipe.row_cnt, pipe.col_idx, pipe.ws3)
+            pbs.block_mask(pipe.p_kbar, Q, pipe.Kp, pipe.mask_bits, pipe.row_cnt, pipe.col_idx, pipe.ws3)
             mark(3)
             pbs.attn_fwd(p, Q, pipe.Kp, pipe.Vt, None, pipe.kidx, pipe.row_cnt, pipe.col_idx, pipe.Op, ws=pipe.ws4)
         mark(4)

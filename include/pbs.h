@@ -76,8 +76,11 @@ typedef enum { PBS_F32 = 0, PBS_BF16 = 1 } pbs_dtype;
  * PBS_FLAG_RUNNING_MAX_ONLY: pbs_attn_fwd evaluates every query block with the running-maximum recurrence of
  *   Algorithm 1 as printed (m moves and O, l are rescaled); for bf16, d = 128, block = 128 this leaves out the first
  *   pass, which keeps a fixed softmax reference per query.  Same result up to rounding; slower.
+ * PBS_FLAG_KBAR_IN_WS: the workspace given to pbs_block_mask already holds the block means of Kp, left there by
+ *   the pbs_segment_permute call that wrote this Kp (see its `ws`); pbs_block_mask then does not read Kp at all.
  */
-enum { PBS_FLAG_FORCE_FIRST_BLOCK = 1u, PBS_FLAG_TOKEN_ORDER_COPY = 2u, PBS_FLAG_RUNNING_MAX_ONLY = 4u };
+enum { PBS_FLAG_FORCE_FIRST_BLOCK = 1u, PBS_FLAG_TOKEN_ORDER_COPY = 2u, PBS_FLAG_RUNNING_MAX_ONLY = 4u,
+       PBS_FLAG_KBAR_IN_WS = 8u };
 
 typedef enum {
     PBS_STAGE_KEY_SCORES = 1,
@@ -145,6 +148,10 @@ size_t pbs_key_scores_static_scratch_bytes(void);
  *     baseline of the appendix "Block Selection in PBS-Attn": K' = K, V' = V).  NaN scores are not supported.
  *   kidx   [batch,h_kv,n] int32, written.
  *   Kp, Vt written; pass both NULL to compute kidx only (K and V may then be NULL too).
+ *   ws: optional.  NULL: nothing more.  Otherwise at least pbs_workspace_bytes(p, PBS_STAGE_BLOCK_MASK) bytes,
+ *   256-byte aligned (else PBS_ERR_WORKSPACE): the block means of K' that Algorithm 2 starts from are written there
+ *   while K' is gathered (the first step of pbs_block_mask moved up one stage, so that K' is not read again for it);
+ *   hand the same memory to pbs_block_mask with PBS_FLAG_KBAR_IN_WS set.  Ignored when Kp is NULL.
  */
 pbs_status pbs_segment_permute(const pbs_problem *p, const float *scores, const void *K, const void *V,
                                int32_t *kidx, void *Kp, void *Vt, void *ws, size_t ws_bytes, void *stream);

@@ -15,7 +15,7 @@ _lib = None
 
 PBS_F32, PBS_BF16 = 0, 1
 STAGE_KEY_SCORES, STAGE_SEGMENT_PERMUTE, STAGE_BLOCK_MASK, STAGE_ATTN_FWD, STAGE_UNPERMUTE = 1, 2, 3, 4, 5
-FLAG_FORCE_FIRST_BLOCK, FLAG_TOKEN_ORDER_COPY, FLAG_RUNNING_MAX_ONLY = 1, 2, 4
+FLAG_FORCE_FIRST_BLOCK, FLAG_TOKEN_ORDER_COPY, FLAG_RUNNING_MAX_ONLY, FLAG_KBAR_IN_WS = 1, 2, 4, 8
 
 EXPORTS = ["pbs_status_string", "pbs_validate", "pbs_workspace_bytes", "pbs_vt_bytes", "pbs_key_scores",
            "pbs_segment_permute", "pbs_permute_rows", "pbs_block_mask", "pbs_attn_fwd", "pbs_unpermute",
@@ -172,7 +172,7 @@ def key_scores_static(p, Q, K, scores=None):
     return scores
 
 
-def segment_permute(p, scores, K, V, kidx=None, Kp=None, Vt=None, indices_only=False):
+def segment_permute(p, scores, K, V, kidx=None, Kp=None, Vt=None, indices_only=False, ws=None):
     dev = (K if K is not None else scores).device
     if kidx is None:
         kidx = alloc_kidx(p, dev)
@@ -182,7 +182,8 @@ def segment_permute(p, scores, K, V, kidx=None, Kp=None, Vt=None, indices_only=F
         if Vt is None:
             Vt = alloc_vt(p, dev)
     _check(load_library().pbs_segment_permute(ctypes.byref(p), _ptr(scores), _ptr(K), _ptr(V), _ptr(kidx), _ptr(Kp),
-                                              _ptr(Vt), None, 0, _stream()), "pbs_segment_permute")
+                                              _ptr(Vt), _ptr(ws), 0 if ws is None else ws.numel(), _stream()),
+           "pbs_segment_permute")
     return kidx, Kp, Vt
 
 
@@ -268,6 +269,8 @@ class Pipeline:
 
     def __init__(self, p, device="cuda", use_sigma=False):
         self.p = p
+        self.p_kbar = pbs_problem.from_buffer_copy(p)
+        self.p_kbar.flags |= FLAG_KBAR_IN_WS
         T, dt = T_of(p), torch_dtype(p)
         self.scores = torch.empty((p.batch, p.h_kv, p.n), dtype=torch.float32, device=device)
         self.kidx = alloc_kidx(p, device)
@@ -286,9 +289,10 @@ class Pipeline:
     def run(self, Q, K, V, qidx=None):
         p = self.p
         key_scores(p, Q, K, self.scores, self.ws1)
-        segment_permute(p, self.scores, K, V, self.kidx, self.Kp, self.Vt)
+        # the block means of K' that Algorithm 2 starts from come out of the gather (PBS_FLAG_KBAR_IN_WS)
+        segment_permute(p, self.scores, K, V, self.kidx, self.Kp, self.Vt, ws=self.ws3)
         Qp = Q if qidx is None else permute_rows(p, Q, qidx, self.Qp)
-        block_mask(p, Qp, self.Kp, self.mask_bits, self.row_cnt, self.col_idx, self.ws3)
+        block_mask(self.p_kbar, Qp, self.Kp, self.mask_bits, self.row_cnt, self.col_idx, self.ws3)
         attn_fwd(p, Qp, self.Kp, self.Vt, qidx, self.kidx, self.row_cnt, self.col_idx, self.Op, ws=self.ws4)
         return unpermute(p, self.Op, qidx, self.O)
 

@@ -16,12 +16,13 @@
 namespace pbs {
 
 // ---------------------------------------------------------------------------------------------
-// grid = (T, heads); E = input element type.  TRANSPOSED: write out[head][e][T] instead of out[head][i][e].
+// grid = (T, heads); E = input element type.  TRANSPOSED: write out[head][e][Ts] (row stride Ts >= T) instead of
+// out[head][i][e].
 // 256 threads: thread (cg = tid % cpr, rg = tid / cpr) sums its 16-byte column group over rows rg, rg+RG, ...
 // ---------------------------------------------------------------------------------------------
 template <typename E, bool TRANSPOSED>
 __global__ __launch_bounds__(256) void pool_kernel(const E *__restrict__ X, double *__restrict__ out, int n, int d,
-                                                   int block, int T)
+                                                   int block, int T, int Ts)
 {
     constexpr int VEC = 16 / sizeof(E);
     typedef E vec_t __attribute__((ext_vector_type(VEC)));
@@ -39,7 +40,7 @@ __global__ __launch_bounds__(256) void pool_kernel(const E *__restrict__ X, doub
             double s = 0.0;
             for (int row = lo; row < hi; ++row) s += (double)ElemTraits<E>::to_float(X[(head * n + row) * (size_t)d + e]);
             const double mean = s / (double)(hi - lo);
-            if (TRANSPOSED) out[(head * d + e) * (size_t)T + i] = mean;
+            if (TRANSPOSED) out[(head * d + e) * (size_t)Ts + i] = mean;
             else out[(head * T + i) * (size_t)d + e] = mean;
         }
         return;
@@ -71,14 +72,17 @@ __global__ __launch_bounds__(256) void pool_kernel(const E *__restrict__ X, doub
         double s = 0.0;
         for (int q = 0; q < RG; ++q) s += red[(q * cpr + c) * VEC + u];
         const double mean = s / (double)(hi - lo);
-        if (TRANSPOSED) out[(head * d + e) * (size_t)T + i] = mean;
+        if (TRANSPOSED) out[(head * d + e) * (size_t)Ts + i] = mean;
         else out[(head * T + i) * (size_t)d + e] = mean;
     }
 }
 
 // ---------------------------------------------------------------------------------------------
 // Selection.  One workgroup per (kv head, chunk of RB query heads of its group, query block i): the RB rows
-// share the allowed columns and the pooled keys, so every Kbar value fetched feeds RB logits.  After the
+// share the allowed columns and the pooled keys.  The logits are register-tiled: a thread owns four neighbouring
+// columns of all RB rows, so the two 16-byte loads that bring one feature of its four pooled keys and the (at most)
+// two 16-byte LDS reads that bring that feature of the RB pooled queries feed 4 * RB multiply-add pairs; every sum
+// still runs over the features in ascending order with separate multiplications and additions.  After the
 // logits, wave w owns row w and finishes it alone (no workgroup barriers): softmax, then the smallest
 // probability v* that is still kept, found by bisection instead of a sort.
 //
@@ -108,17 +112,18 @@ __device__ inline MassCount mass_at_least(const double *pr, int ni64, int lane, 
     return {wave_sum_dpp(acc), cnt};
 }
 
+// (the LDS a workgroup needs admits four of them per compute unit at T = 1024: registers for four waves per SIMD)
 template <int RB, typename E>
-__global__ __launch_bounds__(64 * RB) void select_kernel(const E *__restrict__ Qp,           // [bhq][n][d]
-                                                         const double *__restrict__ KbarT,   // [bhkv][d][T]
+__global__ __launch_bounds__(64 * RB) __attribute__((amdgpu_waves_per_eu(1, 4))) void select_kernel(const E *__restrict__ Qp,           // [bhq][n][d]
+                                                         const double *__restrict__ KbarT,   // [bhkv][d][Ts]
                                                          uint64_t *__restrict__ mask_bits,
                                                          int32_t *__restrict__ row_cnt,
-                                                         int32_t *__restrict__ col_idx, Geo g, int chunks, int Tpad)
+                                                         int32_t *__restrict__ col_idx, Geo g, int chunks, int Tpad, int Ts)
 {
     constexpr int THREADS = 64 * RB;
     extern __shared__ __align__(16) unsigned char smem_raw[];
     double *prob = reinterpret_cast<double *>(smem_raw);             // [RB][Tpad]
-    __shared__ __align__(16) double qs[RB][128];                     // block means of the RB query rows (d <= 128)
+    __shared__ __align__(16) double qs[128][RB];                     // block means of the RB query rows, feature-major
 
     const int i = blockIdx.x;
     const int bhk = blockIdx.y / chunks, chunk = blockIdx.y % chunks;
@@ -140,7 +145,7 @@ __global__ __launch_bounds__(64 * RB) void select_kernel(const E *__restrict__ Q
             for (int e = lane; e < g.d; e += 64) {
                 double s = 0.0;
                 for (int row = lo; row < hi; ++row) s += (double)ElemTraits<E>::to_float(X[(size_t)row * g.d + e]);
-                qs[w][e] = s / (double)(hi - lo);
+                qs[e][w] = s / (double)(hi - lo);
             }
         }
     } else {
@@ -175,28 +180,53 @@ __global__ __launch_bounds__(64 * RB) void select_kernel(const E *__restrict__ Q
             for (int u = 0; u < VEC; ++u) acc[u] += __shfl_xor(acc[u], o, 64);
         if (rg == 0)
 #pragma unroll
-            for (int u = 0; u < VEC; ++u) qs[w][cg * VEC + u] = acc[u] / (double)(hi - lo);
+            for (int u = 0; u < VEC; ++u) qs[cg * VEC + u][w] = acc[u] / (double)(hi - lo);
     }
     __syncthreads();
 
-    // logits, plain multiply-then-add in the order e = 0..d-1
-    const double *kt = KbarT + (size_t)bhk * g.d * g.T;
-    for (int j = tid; j < ni; j += THREADS) {
-        double acc[RB];
+    // logits: fused multiply-adds in the order e = 0..d-1; columns j .. j + 3 of every row per thread (columns at or
+    // beyond ni are computed from whatever the padded Kbar rows hold and dropped).  The pooled keys of the next four
+    // features are requested before the current four are multiplied.
+    const double *kt = KbarT + (size_t)bhk * g.d * Ts;
+    typedef double double2v __attribute__((ext_vector_type(2)));
+    for (int j = 4 * tid; j < ni; j += 4 * THREADS) {
+        double acc[RB][4];
 #pragma unroll
-        for (int row = 0; row < RB; ++row) acc[row] = 0.0;
-        for (int e = 0; e < g.d; e += 8) {
-            double kv[8];
+        for (int row = 0; row < RB; ++row)
 #pragma unroll
-            for (int u = 0; u < 8; ++u) kv[u] = kt[(size_t)(e + u) * g.T + j];
+            for (int c = 0; c < 4; ++c) acc[row][c] = 0.0;
+        double2v cur[4][2], nxt[4][2];
+        auto fetch = [&](double2v (&kv)[4][2], int e) {
 #pragma unroll
-            for (int u = 0; u < 8; ++u)
+            for (int u = 0; u < 4; ++u) {
+                const double2v *src = reinterpret_cast<const double2v *>(kt + (size_t)(e + u) * Ts + j);
+                kv[u][0] = src[0];
+                kv[u][1] = src[1];
+            }
+        };
+        fetch(cur, 0);
+        for (int e = 0; e < g.d; e += 4) {
+            fetch(nxt, e + 4 < g.d ? e + 4 : e);             // the last round re-reads its own features (unused)
 #pragma unroll
-                for (int row = 0; row < RB; ++row)
-                    acc[row] = __dadd_rn(acc[row], __dmul_rn(qs[row][e + u], kv[u]));
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int row = 0; row < RB; ++row) {
+                    const double q = qs[e + u][row];
+#pragma unroll
+                    for (int c = 0; c < 4; ++c)
+                        acc[row][c] = __builtin_fma(q, cur[u][c >> 1][c & 1], acc[row][c]);
+                }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                cur[u][0] = nxt[u][0];
+                cur[u][1] = nxt[u][1];
+            }
         }
 #pragma unroll
-        for (int row = 0; row < RB; ++row) prob[row * Tpad + j] = __dmul_rn(acc[row], (double)g.scale);
+        for (int row = 0; row < RB; ++row)
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                if (j + c < ni) prob[row * Tpad + j + c] = __dmul_rn(acc[row][c], (double)g.scale);
     }
     __syncthreads();
 
@@ -299,6 +329,7 @@ static pbs_status launch_select(const E *Qp, const double *KbarT, uint64_t *mask
 {
     const int chunks = (g.r + RB - 1) / RB;
     const int Tpad = (g.T + 63) & ~63;
+    const int Ts = kbar_stride(g.T);
     const size_t lds = (size_t)RB * Tpad * sizeof(double);
     static std::atomic<unsigned long long> lds_raised{0};
     if (lds > 32 * 1024) {
@@ -307,13 +338,26 @@ static pbs_status launch_select(const E *Qp, const double *KbarT, uint64_t *mask
         if (st != PBS_OK) return st;
     }
     return launch((select_kernel<RB, E>), dim3(g.T, g.batch * g.h_kv * chunks), dim3(64 * RB), lds, s, Qp, KbarT,
-                       mask_bits, row_cnt, col_idx, g, chunks, Tpad);
+                       mask_bits, row_cnt, col_idx, g, chunks, Tpad, Ts);
+}
+
+// Block means of K' into KbarT ([kv head][feature][kbar_stride(T)] fp64); also called by pbs_segment_permute for the
+// shapes its gather kernel does not pool on the way.
+pbs_status launch_pool_keys(const pbs_problem *p, const Geo &g, const void *Kp, double *KbarT, hipStream_t s)
+{
+    const int nk = g.batch * g.h_kv;
+    if (p->dtype == PBS_BF16)
+        return launch((pool_kernel<bf16_t, true>), dim3(g.T, nk), dim3(256), 0, s, (const bf16_t *)Kp, KbarT, g.n, g.d,
+                      g.block, g.T, kbar_stride(g.T));
+    return launch((pool_kernel<float, true>), dim3(g.T, nk), dim3(256), 0, s, (const float *)Kp, KbarT, g.n, g.d, g.block,
+                  g.T, kbar_stride(g.T));
 }
 
 size_t ws_block_mask(const pbs_problem *p)
 {
     const Geo g = make_geo(p);
-    return align_up((size_t)g.batch * g.h_kv * g.T * g.d * sizeof(double), kWsAlign);   // pooled K', fp64, d-major
+    // pooled K', fp64, feature-major, rows padded to kbar_stride(T) columns
+    return align_up((size_t)g.batch * g.h_kv * kbar_stride(g.T) * g.d * sizeof(double), kWsAlign);
 }
 
 }  // namespace pbs
@@ -331,17 +375,13 @@ extern "C" pbs_status pbs_block_mask(const pbs_problem *p, const void *Qp, const
     const Geo g = make_geo(p);
     hipStream_t s = (hipStream_t)stream;
     double *KbarT = reinterpret_cast<double *>(ws);
-    const int nk = g.batch * g.h_kv;
+    if (!(p->flags & PBS_FLAG_KBAR_IN_WS) && (st = launch_pool_keys(p, g, Kp, KbarT, s)) != PBS_OK) return st;
     if (p->dtype == PBS_BF16) {
-        if ((st = launch((pool_kernel<bf16_t, true>), dim3(g.T, nk), dim3(256), 0, s, (const bf16_t *)Kp, KbarT, g.n,
-                           g.d, g.block, g.T)) != PBS_OK) return st;
         const bf16_t *Q = (const bf16_t *)Qp;
         if (g.r >= 3) return launch_select<4>(Q, KbarT, mask_bits, row_cnt, col_idx, g, s);
         if (g.r == 2) return launch_select<2>(Q, KbarT, mask_bits, row_cnt, col_idx, g, s);
         return launch_select<1>(Q, KbarT, mask_bits, row_cnt, col_idx, g, s);
     }
-    if ((st = launch((pool_kernel<float, true>), dim3(g.T, nk), dim3(256), 0, s, (const float *)Kp, KbarT, g.n, g.d,
-                       g.block, g.T)) != PBS_OK) return st;
     const float *Q = (const float *)Qp;
     if (g.r >= 3) return launch_select<4>(Q, KbarT, mask_bits, row_cnt, col_idx, g, s);
     if (g.r == 2) return launch_select<2>(Q, KbarT, mask_bits, row_cnt, col_idx, g, s);

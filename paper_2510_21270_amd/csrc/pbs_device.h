@@ -54,6 +54,10 @@ __host__ __device__ inline int first_masked_col(int i, const Geo &g)
 // element (group gi, feature e, key k of the group) of a block sits at ((gi * d + e) * vt_group + k).
 __host__ __device__ inline int vt_group(int block) { return block < 32 ? block : 32; }
 
+// The pooled keys are kept feature-major, [kv head][feature][kbar_stride(T)] fp64: the columns of one feature padded
+// to a multiple of four, so that four neighbouring columns are two aligned 16-byte pieces.
+__host__ __device__ inline int kbar_stride(int T) { return (T + 3) & ~3; }
+
 template <typename T> struct ElemTraits;
 template <> struct ElemTraits<float> {
     __device__ static inline float to_float(float v) { return v; }

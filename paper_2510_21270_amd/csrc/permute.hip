@@ -133,6 +133,85 @@ __global__ __launch_bounds__(256) void move_rows_kernel(const uintx4 *__restrict
 }
 
 // ---------------------------------------------------------------------------------------------
+// The row gather of K' for 2-byte storage (move_rows_kernel<false> with the same grid, ranges and token-order copy)
+// that also leaves the block means of K' behind, as Algorithm 2 needs them next: kbarT[head][feature][Ts] fp64.
+// A workgroup owns whole key blocks (its range is a multiple of block * cpr chunks, and a block is a whole number of
+// 1024-chunk batches), a thread always meets the same 16-byte column group, so it adds up its rows' eight features in
+// fp64 registers while the rows pass through (sums of bf16 values are exact in fp64 in any order), and at the end of
+// every block the 256 / cpr row slots of a column meet in LDS.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void gather_pool_kernel(const uintx4 *__restrict__ src,
+                                                          const int32_t *__restrict__ idx, uintx4 *__restrict__ dst,
+                                                          int n, int cpr_log2, size_t copy_stride,
+                                                          double *__restrict__ kbarT, int block, int Ts)
+{
+    constexpr int U = 4;
+    __shared__ double red[256 * 8];
+    const size_t head = (size_t)blockIdx.y * n;
+    const uint32_t chunks = (uint32_t)n << cpr_log2;
+    const uint32_t cpr = 1u << cpr_log2, cmask = cpr - 1u;
+    const bool plain = copy_stride != 0 && (blockIdx.x & 1);
+    const uint32_t wg = copy_stride ? blockIdx.x >> 1 : blockIdx.x, nwg = copy_stride ? gridDim.x >> 1 : gridDim.x;
+    const uintx4 *hsrc = src + (head << cpr_log2);
+    uintx4 *hdst = dst + (head << cpr_log2) + (plain ? copy_stride : 0);
+    const int32_t *hidx = (idx && !plain) ? idx + head : nullptr;
+    const uint32_t batch = U * 256;
+    const uint32_t cpb = (uint32_t)block << cpr_log2;        // chunks per key block, a multiple of batch
+    const uint32_t per = ((chunks + nwg - 1) / nwg + cpb - 1) / cpb * cpb;
+    const uint32_t begin = min(wg * per, chunks), end = min(begin + per, chunks);
+    const int d = 8 << cpr_log2;
+    double acc[8];
+#pragma unroll
+    for (int x = 0; x < 8; ++x) acc[x] = 0.0;
+    for (uint32_t base = begin; base < end; base += batch) {
+        int32_t other[U];
+        uintx4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t c = base + threadIdx.x + u * 256;
+            other[u] = c < end ? (hidx ? hidx[c >> cpr_log2] : (int32_t)(c >> cpr_log2)) : -1;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t c = base + threadIdx.x + u * 256;
+            v[u] = uintx4{0u, 0u, 0u, 0u};
+            if (other[u] >= 0 && other[u] < n) v[u] = hsrc[((uint32_t)other[u] << cpr_log2) + (c & cmask)];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t c = base + threadIdx.x + u * 256;
+            if (c < end) hdst[c] = v[u];
+        }
+        if (plain) continue;                                  // uniform: the token-order copy is not pooled
+#pragma unroll
+        for (int u = 0; u < U; ++u)                           // rows past the end were loaded as zeros
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+                acc[2 * x] += (double)__uint_as_float(v[u][x] << 16);
+                acc[2 * x + 1] += (double)__uint_as_float(v[u][x] & 0xffff0000u);
+            }
+        const uint32_t done = base + batch - begin;
+        if (done % cpb == 0 || base + batch >= end) {         // uniform: a key block is complete
+            const int blk = (int)((base >> cpr_log2) / (uint32_t)block);
+            const int rows = min(block, n - blk * block);
+#pragma unroll
+            for (int x = 0; x < 8; ++x) {
+                red[threadIdx.x * 8 + x] = acc[x];
+                acc[x] = 0.0;
+            }
+            __syncthreads();
+            if ((int)threadIdx.x < d) {
+                const int e = threadIdx.x;
+                double s = 0.0;
+                for (uint32_t q = 0; q < 256 / cpr; ++q) s += red[(q * cpr + (e >> 3)) * 8 + (e & 7)];
+                kbarT[((size_t)blockIdx.y * d + e) * Ts + blk] = s / (double)rows;
+            }
+            __syncthreads();
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // V' in the block-transposed layout Vt[bh][j][e][c] = V[bh][kidx[j*block + c]][e] (zero for slots >= n).
 // One workgroup per (key block j, bh): gathered rows go to LDS with coalesced 16-byte reads, the tile is
 // read back column-wise in 4-byte words and leaves as 16-byte pieces of Vt rows (VEC keys of one feature),
@@ -236,6 +315,9 @@ static dim3 move_grid(int n, int cpr, int nbh)
     return dim3((unsigned)bx, (unsigned)nbh);
 }
 
+size_t ws_block_mask(const pbs_problem *p);
+pbs_status launch_pool_keys(const pbs_problem *p, const Geo &g, const void *Kp, double *KbarT, hipStream_t s);
+
 }  // namespace pbs
 
 using namespace pbs;
@@ -244,11 +326,12 @@ extern "C" pbs_status pbs_segment_permute(const pbs_problem *p, const float *sco
                                           int32_t *kidx, void *Kp, void *Vt, void *ws, size_t ws_bytes,
                                           void *stream)
 {
-    (void)ws; (void)ws_bytes;
     pbs_status st = validate(p);
     if (st != PBS_OK) return st;
     if (!kidx) return PBS_ERR_NULL;
     if ((Kp == nullptr) != (Vt == nullptr)) return PBS_ERR_NULL;
+    if (ws && Kp && ((reinterpret_cast<uintptr_t>(ws) & (kWsAlign - 1)) != 0 || ws_bytes < ws_block_mask(p)))
+        return PBS_ERR_WORKSPACE;
     if (Kp && (!K || !V)) return PBS_ERR_NULL;
     if (Kp && (!aligned16(K) || !aligned16(V) || !aligned16(Kp) || !aligned16(Vt))) return PBS_ERR_SHAPE;
     const Geo g = make_geo(p);
@@ -274,8 +357,18 @@ extern "C" pbs_status pbs_segment_permute(const pbs_problem *p, const float *sco
     const size_t vt_half = (size_t)nbh * g.T * g.d * g.block;           // elements
     dim3 mg = move_grid(g.n, cpr, nbh);
     if (token_copy) mg.x *= 2;
-    if ((st = launch(move_rows_kernel<false>, mg, dim3(256), 0, s, (const uintx4 *)K, (const int32_t *)kidx,
-                       (uintx4 *)Kp, g.n, ilog2(cpr), token_copy ? tok_rows * cpr : (size_t)0)) != PBS_OK) return st;
+    // with a workspace, the block means of K' are left there for pbs_block_mask: by the gather itself where a key
+    // block is a whole number of its 1024-chunk batches (2-byte storage), by the pooling kernel otherwise
+    double *kbarT = reinterpret_cast<double *>(ws);
+    const bool pool_on_the_way = kbarT && p->dtype == PBS_BF16 && (g.block * cpr) % 1024 == 0;
+    if (pool_on_the_way)
+        st = launch(gather_pool_kernel, mg, dim3(256), 0, s, (const uintx4 *)K, (const int32_t *)kidx, (uintx4 *)Kp, g.n,
+                    ilog2(cpr), token_copy ? tok_rows * cpr : (size_t)0, kbarT, g.block, kbar_stride(g.T));
+    else
+        st = launch(move_rows_kernel<false>, mg, dim3(256), 0, s, (const uintx4 *)K, (const int32_t *)kidx,
+                    (uintx4 *)Kp, g.n, ilog2(cpr), token_copy ? tok_rows * cpr : (size_t)0);
+    if (st != PBS_OK) return st;
+    if (kbarT && !pool_on_the_way && (st = launch_pool_keys(p, g, Kp, kbarT, s)) != PBS_OK) return st;
     const dim3 vg(token_copy ? 2 * g.T : g.T, nbh);
     if (p->dtype == PBS_BF16) {
         const size_t lds = (size_t)g.block * g.d * 2 + (size_t)(g.block / 8) * (64 / (vt_group(g.block) / 8)) * 4;   // tile + skew

@@ -160,6 +160,37 @@ def test_coverage_of_the_selected_blocks(lib, oracle, name, sigma):
     assert want.mean() > 0.5                            # tau >= 0.7 on pooled scores keeps most of the true mass here
 
 
+@pytest.mark.parametrize("token_copy", [False, True])
+@pytest.mark.parametrize("name", CASES + ["bf16_even"])
+def test_block_means_left_by_the_permutation_stage(lib, oracle, name, token_copy):
+    # pbs_segment_permute with a workspace also leaves the fp64 block means of K' there (by the gather kernel itself
+    # for 2-byte storage and blocks of whole 1024-chunk batches, by the pooling kernel otherwise); pbs_block_mask with
+    # PBS_FLAG_KBAR_IN_WS then must select exactly what the oracle selects, without reading K' (a poisoned K' is passed)
+    w, res = _oracle_run(oracle, name, False)
+    p = make_problem(w, flags=w.flags | (pbs.FLAG_TOKEN_ORDER_COPY if token_copy else 0))
+    pk = make_problem(w, flags=p.flags | pbs.FLAG_KBAR_IN_WS)
+    ws = pbs.alloc_workspace(p, pbs.STAGE_BLOCK_MASK)
+    ws.fill_(0xFF)                                                      # NaN patterns wherever nothing is written
+    kidx, Kp, Vt = pbs.segment_permute(p, torch.from_numpy(res["s_handoff"]).cuda(), to_dev(w.K, w.dtype),
+                                       to_dev(w.V, w.dtype), ws=ws)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(kidx.cpu().numpy(), res["kidx"])
+    np.testing.assert_array_equal(to_host(Kp), res["Kp"].astype(np.float64))
+    poisoned = torch.full_like(Kp, float("nan"))
+    bits, cnt, cols = pbs.block_mask(pk, to_dev(res["Qp"], w.dtype), poisoned, ws=ws)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(mask_from_bits(bits, w.T), res["mask"])
+    np.testing.assert_array_equal(cnt.cpu().numpy(), res["row_cnt"])
+    valid = np.arange(w.T)[None, None, None, :] < res["row_cnt"][..., None]
+    np.testing.assert_array_equal(np.where(valid, cols.cpu().numpy(), -1), res["col_idx"])
+    # a workspace that is too small is refused before anything is launched
+    lib_ = pbs.load_library()
+    import ctypes
+    st = lib_.pbs_segment_permute(ctypes.byref(p), None, Kp.data_ptr(), Kp.data_ptr(), kidx.data_ptr(), Kp.data_ptr(),
+                                  Vt.data_ptr(), ws.data_ptr(), 16, None)
+    assert st == 4
+
+
 @pytest.mark.parametrize("name", CASES)
 def test_pipeline_composed(lib, oracle, name):
     """All five stages chained on the GPU.  GPU scores are only close to the oracle's, so near-tied keys may swap
