@@ -170,11 +170,14 @@ pbs_status pbs_permute_rows(const pbs_problem *p, int32_t heads, const void *X, 
  *   a_i = softmax_j(Qbar_i . Kbar_j * scale) over the columns the extended causal mask C admits:
  *         j < (g(i)+1)*R for a query block inside full segment g(i), j <= i past the last full segment;
  *   stable descending sort (ties: lowest j), cumulative sum, k = min({t : c[t] >= tau} U {n_i}), first k kept.
- * All of this is IEEE fp64 with separate multiplications and additions in the order of the definition (block means:
- * rows ascending for fp32 storage; for bf16 storage any order gives the exact sum), so that the discrete result does
- * not depend on how a machine rounds lower precision.  Two sums are formed in a tree order instead of left to right
- * (the softmax denominator and the partial masses the threshold search compares with tau): a selection can differ
- * from the left-to-right evaluation only if a cumulative mass lies within a few 1e-16 of tau.  Then the blocks of the
+ * All of this is IEEE fp64 in the order of the definition (block means: rows ascending for fp32 storage; for bf16
+ * storage any order gives the exact sum; logits: features ascending), so that the discrete result does not depend
+ * on how a machine rounds lower precision.  Where the evaluation differs from a plain left-to-right one with
+ * separate multiplications and additions, it does so by single roundings: the logits use fused multiply-adds (the
+ * same bits whenever the products are exact, as they are for block means of bf16 values unless one column of a block
+ * spreads over more than about ten binades), and two sums are formed in a tree order (the softmax denominator and
+ * the partial masses the threshold search compares with tau).  A selection can then differ from the plain
+ * evaluation only if a cumulative mass lies within a few 1e-16 of tau.  Then the blocks of the
  * query block's own segment are switched on (Section "Effect of Segment Size": they cannot be skipped); past the
  * last full segment only the diagonal block; and block 0 when PBS_FLAG_FORCE_FIRST_BLOCK is set (Section
  * "Baselines").  Forced blocks do not change k.

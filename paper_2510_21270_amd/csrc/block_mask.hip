@@ -1,7 +1,9 @@
 // pbs_block_mask: Algorithm 2 (MeanPooling block selection) on the permuted (Q', K') plus the forced blocks.
 //
-// Everything that decides the discrete result runs in IEEE fp64 with the plain operation order (no fused
-// multiply-add in the logits), so the mask does not depend on how a machine rounds lower precision:
+// Everything that decides the discrete result runs in IEEE fp64 in the order of the definition, so the mask does not
+// depend on how a machine rounds lower precision (the logits use fused multiply-adds: the same bits as separate
+// operations whenever the products of two block means are exact, which 15 + 15 significant bits plus the exponent
+// spread inside a block's column usually are):
 //   1. pool_kernel     block means of K' (HBM-bound), stored d-major ([head][e][T]) so that the next kernel reads
 //                      them coalesced.  A sum of up to 128 bf16 values is exact in fp64 in any order (8 significant
 //                      bits each; the exponents of one column would have to spread over more than 38 binades to lose
@@ -81,8 +83,8 @@ __global__ __launch_bounds__(256) void pool_kernel(const E *__restrict__ X, doub
 // Selection.  One workgroup per (kv head, chunk of RB query heads of its group, query block i): the RB rows
 // share the allowed columns and the pooled keys.  The logits are register-tiled: a thread owns four neighbouring
 // columns of all RB rows, so the two 16-byte loads that bring one feature of its four pooled keys and the (at most)
-// two 16-byte LDS reads that bring that feature of the RB pooled queries feed 4 * RB multiply-add pairs; every sum
-// still runs over the features in ascending order with separate multiplications and additions.  After the
+// two 16-byte LDS reads that bring that feature of the RB pooled queries feed 4 * RB fused multiply-adds; every sum
+// runs over the features in ascending order.  After the
 // logits, wave w owns row w and finishes it alone (no workgroup barriers): softmax, then the smallest
 // probability v* that is still kept, found by bisection instead of a sort.
 //

@@ -222,3 +222,10 @@ def random_segment_perm(seed, nbh, n, segment):
         for g in range(G):
             idx[bh, g * segment:(g + 1) * segment] = g * segment + rng.permutation(segment).astype(np.int32)
     return idx
+
+
+def random_query_rows(seed, n, m):
+    """m distinct query positions drawn uniformly from [0, n), ascending (the Random-Query proxy draws its queries at
+    random; the draw is an input of the scoring call, not something the library does)."""
+    rng = _rng(seed, 300)
+    return np.sort(rng.choice(n, size=min(m, n), replace=False)).astype(np.int32)

@@ -17,3 +17,10 @@ def oracle():
     from oracle import pbs_oracle
     pbs_oracle.build()
     return pbs_oracle
+
+
+@pytest.fixture(scope="session")
+def oracle_variants():
+    from oracle import pbs_oracle_variants
+    pbs_oracle_variants.build()
+    return pbs_oracle_variants
