@@ -125,13 +125,31 @@ pbs_status pbs_key_scores(const pbs_problem *p, const void *Q, const void *K, fl
                           void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * The other proxies for the importance score that the paper ablates (Section "The Problem of Information
+ * Fragmentation", heuristic 4; appendix "Task-wise Proxy Sensitivity"): the formula of Eq. 4 with another set of
+ * query rows standing for all queries.
+ *   PBS_PROXY_LAST_BLOCK   the last min(block, n) rows: exactly pbs_key_scores (Last-Block-Query-Attn).
+ *   PBS_PROXY_QUERY_ROWS   the m rows at the positions qrows[0 .. m-1] (device memory, int32, the same positions for
+ *                          every head; 1 <= m <= 128; a position outside [0, n) is clamped into it; a position listed
+ *                          twice counts twice).  With positions drawn at random by the caller: Random-Query-Attn.
+ *   PBS_PROXY_AVG_QUERY    one query: the mean over all n positions of the group-averaged query vectors (the reading
+ *                          taken of Avg-Query-Attn, which the paper only names); Q is read in full.
+ * No causal mask, as in Eq. 4.  Arguments, workspace and precision otherwise as pbs_key_scores.
+ * Errors: as pbs_key_scores, plus PBS_ERR_UNSUPPORTED for an unknown proxy, PBS_ERR_NULL / PBS_ERR_SHAPE for a
+ * missing qrows / an m outside [1, 128].
+ */
+typedef enum { PBS_PROXY_LAST_BLOCK = 0, PBS_PROXY_QUERY_ROWS = 1, PBS_PROXY_AVG_QUERY = 2 } pbs_proxy;
+pbs_status pbs_key_scores_proxy(const pbs_problem *p, int proxy, const int32_t *qrows, int32_t m, const void *Q,
+                                const void *K, float *scores, void *ws, size_t ws_bytes, void *stream);
+
+/*
  * For callers that cannot allocate or pass scratch memory (code under HIP graph capture that owns no workspace,
  * tight serving loops, harnesses that forbid hipMalloc): pbs_key_scores with its scratch memory in a device array
  * that is part of the library image instead of in `ws`.  Same arguments otherwise, same kernels, bit-identical
  * scores.  Allocates nothing and calls no allocating routine.
  *   The array holds pbs_key_scores_static_scratch_bytes() = 4 MiB on every GPU the library runs on, until the
  *   process ends; a problem whose pbs_workspace_bytes(p, PBS_STAGE_KEY_SCORES) is larger is rejected with
- *   PBS_ERR_WORKSPACE and nothing is enqueued (the headline layer, 8 kv heads x 131072 keys, needs 1.5 MiB).
+ *   PBS_ERR_WORKSPACE and nothing is enqueued (the headline layer, 8 kv heads x 131072 keys, needs 2.6 MiB).
  *   All calls on one GPU share that GPU's array: two calls whose kernels may overlap in time (different streams,
  *   or different host threads without ordering between their streams) race on it; calls on one stream are safe.
  *   Nothing in the array has to be cleared between calls: every word that a call reads it has written before.

@@ -20,7 +20,7 @@ FLAG_FORCE_FIRST_BLOCK, FLAG_TOKEN_ORDER_COPY, FLAG_RUNNING_MAX_ONLY, FLAG_KBAR_
 EXPORTS = ["pbs_status_string", "pbs_validate", "pbs_workspace_bytes", "pbs_vt_bytes", "pbs_key_scores",
            "pbs_segment_permute", "pbs_permute_rows", "pbs_block_mask", "pbs_attn_fwd", "pbs_unpermute",
            "pbs_mfma_rate_probe", "pbs_key_scores_static", "pbs_key_scores_static_scratch_bytes", "pbs_admitted_lists",
-           "pbs_mass_covered"]
+           "pbs_mass_covered", "pbs_key_scores_proxy"]
 
 
 class PbsError(RuntimeError):
@@ -51,6 +51,7 @@ def load_library():
         lib.pbs_vt_bytes.restype = Z
         lib.pbs_vt_bytes.argtypes = [P]
         lib.pbs_key_scores.argtypes = [P, V, V, V, V, Z, V]
+        lib.pbs_key_scores_proxy.argtypes = [P, ctypes.c_int, V, ctypes.c_int32, V, V, V, V, Z, V]
         lib.pbs_key_scores_static.argtypes = [P, V, V, V, V]
         lib.pbs_key_scores_static_scratch_bytes.restype = Z
         lib.pbs_key_scores_static_scratch_bytes.argtypes = []
@@ -161,6 +162,19 @@ def key_scores(p, Q, K, scores=None, ws=None):
     ws, wp, wn = _ws_args(p, STAGE_KEY_SCORES, ws)
     _check(load_library().pbs_key_scores(ctypes.byref(p), _ptr(Q), _ptr(K), _ptr(scores), wp, wn, _stream()),
            "pbs_key_scores")
+    return scores
+
+
+PROXY_LAST_BLOCK, PROXY_QUERY_ROWS, PROXY_AVG_QUERY = 0, 1, 2
+
+
+def key_scores_proxy(p, proxy, qrows, Q, K, scores=None, ws=None):
+    if scores is None:
+        scores = torch.empty((p.batch, p.h_kv, p.n), dtype=torch.float32, device=K.device)
+    ws, wp, wn = _ws_args(p, STAGE_KEY_SCORES, ws)
+    m = 0 if qrows is None else qrows.numel()
+    _check(load_library().pbs_key_scores_proxy(ctypes.byref(p), proxy, _ptr(qrows), m, _ptr(Q), _ptr(K), _ptr(scores),
+                                               wp, wn, _stream()), "pbs_key_scores_proxy")
     return scores
 
 

@@ -27,8 +27,18 @@ constexpr float kLog2e = 1.4426950408889634f;
 // ------------------------------------------------------------------ MFMA path: prep
 // qsplit[bh][term][row][dswz]: row-major 128 x 128 bf16, 16-byte chunks XOR-permuted by (row & 15) (the lanes of a
 // fragment load then spread over the 16 chunk positions of their rows).  Rows >= bl are zero.
+// qrows: positions of the bl query rows (device memory), or NULL for the last bl rows of the sequence (Eq. 4);
+// positions outside [0, n) are clamped.  qavg != NULL instead: one query row, the fp64 mean over all positions.
+__device__ inline int query_row_position(const int32_t *qrows, int row, int bl, int n)
+{
+    if (!qrows) return n - bl + row;
+    const int pos = qrows[row];
+    return pos < 0 ? 0 : (pos >= n ? n - 1 : pos);
+}
+
 __global__ __launch_bounds__(256) void qhat_split_kernel(const bf16_t *__restrict__ Q, bf16_t *__restrict__ qsplit,
-                                                         Geo g, int bl)
+                                                         Geo g, int bl, const int32_t *__restrict__ qrows,
+                                                         const double *__restrict__ qavg)
 {
     // grid = (kQRows / 8, batch * h_kv): each workgroup converts 8 rows x 128 columns, 4 elements per thread
     const int bh = blockIdx.y;
@@ -39,17 +49,26 @@ __global__ __launch_bounds__(256) void qhat_split_kernel(const bf16_t *__restric
     const int row = blockIdx.x * 8 + (threadIdx.x >> 5);
     const int e0 = (threadIdx.x & 31) * 4;
     float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-    if (row < bl)
-        for (int t = 0; t < g.r; ++t) {
-            const bf16x4 v = *reinterpret_cast<const bf16x4 *>(
-                Q + (((size_t)b * g.h_q + h * g.r + t) * g.n + (g.n - bl + row)) * 128 + e0);
+    float mul_row = mul;
+    if (row < bl) {
+        if (qavg) {                                           // already the mean over heads and positions
 #pragma unroll
-            for (int x = 0; x < 4; ++x) acc[x] += (float)v[x];
+            for (int x = 0; x < 4; ++x) acc[x] = (float)qavg[(size_t)bh * 128 + e0 + x];
+            mul_row = g.scale * kLog2e;
+        } else {
+            const int pos = query_row_position(qrows, row, bl, g.n);
+            for (int t = 0; t < g.r; ++t) {
+                const bf16x4 v = *reinterpret_cast<const bf16x4 *>(
+                    Q + (((size_t)b * g.h_q + h * g.r + t) * g.n + pos) * 128 + e0);
+#pragma unroll
+                for (int x = 0; x < 4; ++x) acc[x] += (float)v[x];
+            }
         }
+    }
     bf16x4 vh, vl;
 #pragma unroll
     for (int x = 0; x < 4; ++x) {
-        const float v = acc[x] * mul;
+        const float v = acc[x] * mul_row;
         vh[x] = (bf16_t)v;
         vl[x] = (bf16_t)(v - (float)vh[x]);
     }
@@ -274,18 +293,62 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 // ------------------------------------------------------------------ generic path (fp64 accumulation)
 template <typename E>
 __global__ __launch_bounds__(256) void qhat_f64_kernel(const E *__restrict__ Q, double *__restrict__ qhat, Geo g,
-                                                       int bl)
+                                                       int bl, const int32_t *__restrict__ qrows,
+                                                       const double *__restrict__ qavg)
 {
     const int bh = blockIdx.x;
     const int b = bh / g.h_kv, h = bh % g.h_kv;
     for (int idx = threadIdx.x; idx < bl * g.d; idx += blockDim.x) {
         const int row = idx / g.d, e = idx % g.d;
+        if (qavg) {
+            qhat[(size_t)bh * bl * g.d + idx] = qavg[(size_t)bh * 128 + e];
+            continue;
+        }
+        const int pos = query_row_position(qrows, row, bl, g.n);
         double acc = 0.0;
         for (int t = 0; t < g.r; ++t)
-            acc += (double)ElemTraits<E>::to_float(
-                Q[(((size_t)b * g.h_q + h * g.r + t) * g.n + (g.n - bl + row)) * g.d + e]);
+            acc += (double)ElemTraits<E>::to_float(Q[(((size_t)b * g.h_q + h * g.r + t) * g.n + pos) * g.d + e]);
         qhat[(size_t)bh * bl * g.d + idx] = acc / (double)g.r;
     }
+}
+
+// ------------------------------------------------------------------ the average query (one proxy of the ablations)
+// partial[bh][chunk][e] = fp64 sum over the chunk's positions and the group's r heads of Q[.., pos, e];
+// grid = (kAvgChunks, nbh), 256 threads: thread (e = tid % d, slot = tid / d) walks the positions slot, slot + 256/d, ..
+constexpr int kAvgChunks = 128;
+
+template <typename E>
+__global__ __launch_bounds__(256) void qavg_partial_kernel(const E *__restrict__ Q, double *__restrict__ partial, Geo g)
+{
+    __shared__ double red[256];
+    const int bh = blockIdx.y, chunk = blockIdx.x;
+    const int b = bh / g.h_kv, h = bh % g.h_kv;
+    const int per = ceil_div(g.n, kAvgChunks);
+    const int lo = chunk * per, hi = min(g.n, lo + per);
+    const int e = threadIdx.x % g.d, slot = threadIdx.x / g.d, slots = 256 / g.d;
+    double acc = 0.0;
+    for (int t = 0; t < g.r; ++t) {
+        const E *Qh = Q + ((size_t)b * g.h_q + h * g.r + t) * (size_t)g.n * g.d;
+        for (int pos = lo + slot; pos < hi; pos += slots) acc += (double)ElemTraits<E>::to_float(Qh[(size_t)pos * g.d + e]);
+    }
+    red[threadIdx.x] = acc;
+    __syncthreads();
+    if ((int)threadIdx.x < g.d) {
+        double s = 0.0;
+        for (int q = 0; q < slots; ++q) s += red[q * g.d + threadIdx.x];
+        partial[((size_t)bh * kAvgChunks + chunk) * 128 + threadIdx.x] = s;
+    }
+}
+
+// qavg[bh][e] = (sum of the partials) / (r * n)
+__global__ __launch_bounds__(128) void qavg_final_kernel(const double *__restrict__ partial, double *__restrict__ qavg,
+                                                         Geo g)
+{
+    const int bh = blockIdx.x, e = threadIdx.x;
+    if (e >= g.d) return;
+    double s = 0.0;
+    for (int c = 0; c < kAvgChunks; ++c) s += partial[((size_t)bh * kAvgChunks + c) * 128 + e];
+    qavg[(size_t)bh * 128 + e] = s / ((double)g.r * (double)g.n);
 }
 
 template <typename E>
@@ -386,35 +449,55 @@ static int sweep_keys_per_wg(const Geo &g)
     return kpw;
 }
 
+// bytes of the average-query region at the end of the workspace: the partial sums and the mean itself
+static size_t ws_avg_query(size_t nbh) { return align_up(nbh * (kAvgChunks + 1) * 128 * sizeof(double), kWsAlign); }
+
+// The generic path sizes its workspace for up to kQRows query rows (the block size may be smaller).
 size_t ws_key_scores(const pbs_problem *p)
 {
     const Geo g = make_geo(p);
     const size_t nbh = (size_t)g.batch * g.h_kv;
-    const int bl = g.block < g.n ? g.block : g.n;
     if (use_mfma(p)) {
         const size_t nwg = ceil_div(g.n, sweep_keys_per_wg(g));
         return align_up(nbh * 2 * kQRows * 128 * sizeof(bf16_t), kWsAlign) +
-               align_up(nbh * nwg * kQRows * sizeof(float2), kWsAlign) + align_up(nbh * kQRows * sizeof(float), kWsAlign);
+               align_up(nbh * nwg * kQRows * sizeof(float2), kWsAlign) + align_up(nbh * kQRows * sizeof(float), kWsAlign) +
+               ws_avg_query(nbh);
     }
     const size_t chunks = ceil_div(g.n, kGenericKeysPerChunk);
-    return align_up(nbh * bl * g.d * sizeof(double), kWsAlign) + align_up(nbh * bl * chunks * sizeof(double2), kWsAlign) +
-           align_up(nbh * bl * sizeof(double2), kWsAlign);
+    const size_t rows = kQRows;
+    return align_up(nbh * rows * g.d * sizeof(double), kWsAlign) + align_up(nbh * rows * chunks * sizeof(double2), kWsAlign) +
+           align_up(nbh * rows * sizeof(double2), kWsAlign) + ws_avg_query(nbh);
 }
 
+// The average query of every kv head into qavg (fp64, 128 doubles per head), through `partial`.
 template <typename E>
-static pbs_status run_generic(const pbs_problem *p, const Geo &g, const void *Q, const void *K, float *scores,
-                              char *ws, hipStream_t s)
+static pbs_status run_qavg(const Geo &g, const void *Q, double *partial, double *qavg, hipStream_t s)
 {
     const int nbh = g.batch * g.h_kv;
-    const int bl = g.block < g.n ? g.block : g.n;
+    pbs_status st;
+    if ((st = launch(qavg_partial_kernel<E>, dim3(kAvgChunks, nbh), dim3(256), 0, s, (const E *)Q, partial, g)) != PBS_OK)
+        return st;
+    return launch(qavg_final_kernel, dim3(nbh), dim3(128), 0, s, (const double *)partial, qavg, g);
+}
+
+// bl query rows: the last bl of the sequence (qrows == NULL), the listed ones, or (avg) the one average query.
+template <typename E>
+static pbs_status run_generic(const pbs_problem *p, const Geo &g, const void *Q, const void *K, float *scores,
+                              char *ws, int bl, const int32_t *qrows, bool avg, hipStream_t s)
+{
+    const int nbh = g.batch * g.h_kv;
     const int chunks = ceil_div(g.n, kGenericKeysPerChunk);
     double *qhat = reinterpret_cast<double *>(ws);
-    ws += align_up((size_t)nbh * bl * g.d * sizeof(double), kWsAlign);
+    ws += align_up((size_t)nbh * kQRows * g.d * sizeof(double), kWsAlign);
     double2 *partial = reinterpret_cast<double2 *>(ws);
-    ws += align_up((size_t)nbh * bl * chunks * sizeof(double2), kWsAlign);
+    ws += align_up((size_t)nbh * kQRows * chunks * sizeof(double2), kWsAlign);
     double2 *stats = reinterpret_cast<double2 *>(ws);
+    ws += align_up((size_t)nbh * kQRows * sizeof(double2), kWsAlign);
+    double *avg_partial = reinterpret_cast<double *>(ws), *qavg = avg_partial + (size_t)nbh * kAvgChunks * 128;
     pbs_status st;
-    if ((st = launch(qhat_f64_kernel<E>, dim3(nbh), dim3(256), 0, s, (const E *)Q, qhat, g, bl)) != PBS_OK) return st;
+    if (avg && (st = run_qavg<E>(g, Q, avg_partial, qavg, s)) != PBS_OK) return st;
+    if ((st = launch(qhat_f64_kernel<E>, dim3(nbh), dim3(256), 0, s, (const E *)Q, qhat, g, bl, qrows,
+                     (const double *)(avg ? qavg : nullptr))) != PBS_OK) return st;
     if ((st = launch(scores_stats_f64_kernel<E>, dim3(chunks, bl, nbh), dim3(256), 0, s, (const E *)K, qhat, partial,
                        g, bl, kGenericKeysPerChunk)) != PBS_OK) return st;
     if ((st = launch(scores_merge_f64_kernel, dim3(nbh), dim3(128), 0, s, partial, stats, bl, chunks)) != PBS_OK) return st;
@@ -428,19 +511,22 @@ static pbs_status run_generic(const pbs_problem *p, const Geo &g, const void *Q,
 
 using namespace pbs;
 
-// Everything after the argument checks: the launches of one pbs_key_scores call with its scratch memory at `ws`.
-static pbs_status enqueue_key_scores(const pbs_problem *p, const void *Q, const void *K, float *scores, void *ws,
-                                     hipStream_t s)
+// Everything after the argument checks: the launches of one scoring call with its scratch memory at `ws`.
+// proxy: which query rows stand for all queries (pbs_proxy); qrows / m only for PBS_PROXY_QUERY_ROWS.
+static pbs_status enqueue_key_scores(const pbs_problem *p, int proxy, const int32_t *qrows, int m, const void *Q,
+                                     const void *K, float *scores, void *ws, hipStream_t s)
 {
     pbs_status st;
     const Geo g = make_geo(p);
     char *w = reinterpret_cast<char *>(ws);
+    const bool avg = proxy == PBS_PROXY_AVG_QUERY;
+    const int bl = avg ? 1 : (proxy == PBS_PROXY_QUERY_ROWS ? m : (g.block < g.n ? g.block : g.n));
+    if (proxy != PBS_PROXY_QUERY_ROWS) qrows = nullptr;
     if (!use_mfma(p)) {
-        if (p->dtype == PBS_BF16) return run_generic<bf16_t>(p, g, Q, K, scores, w, s);
-        return run_generic<float>(p, g, Q, K, scores, w, s);
+        if (p->dtype == PBS_BF16) return run_generic<bf16_t>(p, g, Q, K, scores, w, bl, qrows, avg, s);
+        return run_generic<float>(p, g, Q, K, scores, w, bl, qrows, avg, s);
     }
     const int nbh = g.batch * g.h_kv;
-    const int bl = g.block < g.n ? g.block : g.n;
     const int kpw = sweep_keys_per_wg(g);
     const int nwg = ceil_div(g.n, kpw);
     bf16_t *qsplit = reinterpret_cast<bf16_t *>(w);
@@ -448,7 +534,11 @@ static pbs_status enqueue_key_scores(const pbs_problem *p, const void *Q, const 
     float2 *partial = reinterpret_cast<float2 *>(w);
     w += align_up((size_t)nbh * nwg * kQRows * sizeof(float2), kWsAlign);
     float *cvec = reinterpret_cast<float *>(w);
-    if ((st = launch(qhat_split_kernel, dim3(kQRows / 8, nbh), dim3(256), 0, s, (const bf16_t *)Q, qsplit, g, bl)) != PBS_OK) return st;
+    w += align_up((size_t)nbh * kQRows * sizeof(float), kWsAlign);
+    double *avg_partial = reinterpret_cast<double *>(w), *qavg = avg_partial + (size_t)nbh * kAvgChunks * 128;
+    if (avg && (st = run_qavg<bf16_t>(g, Q, avg_partial, qavg, s)) != PBS_OK) return st;
+    if ((st = launch(qhat_split_kernel, dim3(kQRows / 8, nbh), dim3(256), 0, s, (const bf16_t *)Q, qsplit, g, bl, qrows,
+                     (const double *)(avg ? qavg : nullptr))) != PBS_OK) return st;
     if ((st = launch(scores_sweep1_kernel, dim3(nwg, nbh), dim3(256), 0, s, (const bf16_t *)K, qsplit, partial, g, kpw)) != PBS_OK) return st;
     if ((st = launch(scores_merge_kernel, dim3(nbh), dim3(1024), 0, s, partial, cvec, nwg, bl)) != PBS_OK) return st;
     return launch(scores_sweep2_kernel, dim3(nwg, nbh), dim3(256), 0, s, (const bf16_t *)K, qsplit, cvec, scores,
@@ -463,7 +553,23 @@ extern "C" pbs_status pbs_key_scores(const pbs_problem *p, const void *Q, const 
     if (!Q || !K || !scores) return PBS_ERR_NULL;
     if (!aligned16(Q) || !aligned16(K)) return PBS_ERR_SHAPE;
     if ((st = check_ws(p, PBS_STAGE_KEY_SCORES, ws, ws_bytes)) != PBS_OK) return st;
-    return enqueue_key_scores(p, Q, K, scores, ws, (hipStream_t)stream);
+    return enqueue_key_scores(p, PBS_PROXY_LAST_BLOCK, nullptr, 0, Q, K, scores, ws, (hipStream_t)stream);
+}
+
+extern "C" pbs_status pbs_key_scores_proxy(const pbs_problem *p, int proxy, const int32_t *qrows, int32_t m,
+                                           const void *Q, const void *K, float *scores, void *ws, size_t ws_bytes,
+                                           void *stream)
+{
+    pbs_status st = validate(p);
+    if (st != PBS_OK) return st;
+    if (!Q || !K || !scores) return PBS_ERR_NULL;
+    if (proxy != PBS_PROXY_LAST_BLOCK && proxy != PBS_PROXY_QUERY_ROWS && proxy != PBS_PROXY_AVG_QUERY)
+        return PBS_ERR_UNSUPPORTED;
+    if (proxy == PBS_PROXY_QUERY_ROWS && !qrows) return PBS_ERR_NULL;
+    if (proxy == PBS_PROXY_QUERY_ROWS && (m < 1 || m > kQRows)) return PBS_ERR_SHAPE;
+    if (!aligned16(Q) || !aligned16(K)) return PBS_ERR_SHAPE;
+    if ((st = check_ws(p, PBS_STAGE_KEY_SCORES, ws, ws_bytes)) != PBS_OK) return st;
+    return enqueue_key_scores(p, proxy, qrows, m, Q, K, scores, ws, (hipStream_t)stream);
 }
 
 // ------------------------------------------------------------------ the entry point that allocates nothing
@@ -500,5 +606,5 @@ extern "C" pbs_status pbs_key_scores_static(const pbs_problem *p, const void *Q,
     if (pbs_workspace_bytes(p, PBS_STAGE_KEY_SCORES) > kStaticScratchBytes) return PBS_ERR_WORKSPACE;
     void *ws = static_scratch_of_current_device();
     if (!ws) return PBS_ERR_HIP;
-    return enqueue_key_scores(p, Q, K, scores, ws, (hipStream_t)stream);
+    return enqueue_key_scores(p, PBS_PROXY_LAST_BLOCK, nullptr, 0, Q, K, scores, ws, (hipStream_t)stream);
 }

@@ -160,6 +160,34 @@ def test_coverage_of_the_selected_blocks(lib, oracle, name, sigma):
     assert want.mean() > 0.5                            # tau >= 0.7 on pooled scores keeps most of the true mass here
 
 
+@pytest.mark.parametrize("proxy", ["last", "rows", "rows_few", "avg"])
+@pytest.mark.parametrize("name", ["c1", "bf16_b128", "bf16_b64", "bf16_d64", "bf16_r7"])
+def test_key_scores_from_other_proxies(lib, oracle, oracle_variants, name, proxy):
+    # the proxies the paper ablates: Eq. 4 evaluated on other query rows (random positions, the average query)
+    w, res = _oracle_run(oracle, name, False)
+    p = make_problem(w)
+    Q, K = to_dev(w.Q, w.dtype), to_dev(w.K, w.dtype)
+    if proxy == "last":
+        got = pbs.key_scores_proxy(p, pbs.PROXY_LAST_BLOCK, None, Q, K)
+        want = res["s"]
+    elif proxy == "avg":
+        got = pbs.key_scores_proxy(p, pbs.PROXY_AVG_QUERY, None, Q, K)
+        want = oracle_variants.key_scores_proxy(w.Q, w.K, None)
+    else:
+        rows = wl.random_query_rows(5, w.n, 128 if proxy == "rows" else 3)
+        if proxy == "rows_few":
+            rows = np.array([rows[2], rows[0], rows[2]], dtype=np.int32)      # unsorted, one position twice
+        got = pbs.key_scores_proxy(p, pbs.PROXY_QUERY_ROWS, i32_dev(rows), Q, K)
+        want = oracle_variants.key_scores_proxy(w.Q, w.K, rows)
+    torch.cuda.synchronize()
+    got = got.cpu().numpy().astype(np.float64)
+    rtol = 2e-3 if (w.dtype == "bf16" and w.d == 128) else 1e-5
+    np.testing.assert_allclose(got, want, rtol=rtol, atol=1e-37)
+    np.testing.assert_allclose(got.sum(-1), 1.0, rtol=1e-3)
+    if proxy == "last":                                                        # the same kernels as pbs_key_scores
+        assert torch.equal(pbs.key_scores_proxy(p, pbs.PROXY_LAST_BLOCK, None, Q, K), pbs.key_scores(p, Q, K))
+
+
 @pytest.mark.parametrize("token_copy", [False, True])
 @pytest.mark.parametrize("name", CASES + ["bf16_even"])
 def test_block_means_left_by_the_permutation_stage(lib, oracle, name, token_copy):
