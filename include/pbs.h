@@ -87,7 +87,8 @@ typedef enum {
     PBS_STAGE_SEGMENT_PERMUTE = 2,
     PBS_STAGE_BLOCK_MASK = 3,
     PBS_STAGE_ATTN_FWD = 4,
-    PBS_STAGE_UNPERMUTE = 5
+    PBS_STAGE_UNPERMUTE = 5,
+    PBS_STAGE_QUERY_PERMUTE = 6   /* pbs_query_permutation, an ablation outside Algorithm 1's main setting */
 } pbs_stage;
 
 typedef struct {
@@ -181,6 +182,23 @@ pbs_status pbs_segment_permute(const pbs_problem *p, const float *scores, const 
  */
 pbs_status pbs_permute_rows(const pbs_problem *p, int32_t heads, const void *X, const int32_t *idx, void *Xp,
                             void *stream);
+
+/*
+ * Key-aware query permutation, the ablation of Section "Design Choice: Why Permute Keys but not Queries?" (the
+ * paper's main setting keeps P_sigma = I and needs no call).  Centroids Kbar_j = block means of Kc (the keys the
+ * queries will attend to: K, or K' when the keys are permuted first; valid rows only in a partial last block).  Every
+ * query of a full segment g is assigned to the centroid of highest cosine similarity among those its segment may see,
+ * j < (g+1)*R capped at T, ties to the lowest j; sigma orders the queries of the segment by assigned centroid,
+ * ascending, queries of one centroid in their original order; tokens past the last full segment keep their place.
+ * ("Assigned greedily" is read as: every query takes its single best centroid, no capacity, no reassignment.)
+ *   Q [batch,h_q,n,d]; Kc [batch,h_kv,n,d]; qidx [batch,h_q,n] int32 written, gather form with absolute positions:
+ *   Q'[slot] = Q[qidx[slot]] (pbs_permute_rows), O[qidx[slot]] = O'[slot] (pbs_unpermute).
+ *   ws: pbs_workspace_bytes(p, PBS_STAGE_QUERY_PERMUTE) bytes.  IEEE fp64, features in ascending order, separate
+ *   multiplications and additions: the assignment does not depend on the machine.
+ * Errors: PBS_ERR_NULL, PBS_ERR_SHAPE (misaligned), PBS_ERR_WORKSPACE, the statuses of pbs_validate, PBS_ERR_HIP.
+ */
+pbs_status pbs_query_permutation(const pbs_problem *p, const void *Q, const void *Kc, int32_t *qidx, void *ws,
+                                 size_t ws_bytes, void *stream);
 
 /*
  * Algorithm 2 on the permuted (Q', K'), per query head:

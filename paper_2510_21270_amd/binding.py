@@ -15,12 +15,13 @@ _lib = None
 
 PBS_F32, PBS_BF16 = 0, 1
 STAGE_KEY_SCORES, STAGE_SEGMENT_PERMUTE, STAGE_BLOCK_MASK, STAGE_ATTN_FWD, STAGE_UNPERMUTE = 1, 2, 3, 4, 5
+STAGE_QUERY_PERMUTE = 6
 FLAG_FORCE_FIRST_BLOCK, FLAG_TOKEN_ORDER_COPY, FLAG_RUNNING_MAX_ONLY, FLAG_KBAR_IN_WS = 1, 2, 4, 8
 
 EXPORTS = ["pbs_status_string", "pbs_validate", "pbs_workspace_bytes", "pbs_vt_bytes", "pbs_key_scores",
            "pbs_segment_permute", "pbs_permute_rows", "pbs_block_mask", "pbs_attn_fwd", "pbs_unpermute",
            "pbs_mfma_rate_probe", "pbs_key_scores_static", "pbs_key_scores_static_scratch_bytes", "pbs_admitted_lists",
-           "pbs_mass_covered", "pbs_key_scores_proxy"]
+           "pbs_mass_covered", "pbs_key_scores_proxy", "pbs_query_permutation"]
 
 
 class PbsError(RuntimeError):
@@ -60,6 +61,7 @@ def load_library():
         lib.pbs_block_mask.argtypes = [P, V, V, V, V, V, V, Z, V]
         lib.pbs_attn_fwd.argtypes = [P, V, V, V, V, V, V, V, V, V, V, Z, V]
         lib.pbs_unpermute.argtypes = [P, V, V, V, V]
+        lib.pbs_query_permutation.argtypes = [P, V, V, V, V, Z, V]
         lib.pbs_admitted_lists.argtypes = [P, V, V, V]
         lib.pbs_mass_covered.argtypes = [P, V, V, V, V]
         lib.pbs_mfma_rate_probe.argtypes = [ctypes.c_int, ctypes.c_int, V, Z, ctypes.POINTER(ctypes.c_double), V]
@@ -207,6 +209,15 @@ def permute_rows(p, X, idx, Xp=None):
     _check(load_library().pbs_permute_rows(ctypes.byref(p), X.shape[1], _ptr(X), _ptr(idx), _ptr(Xp), _stream()),
            "pbs_permute_rows")
     return Xp
+
+
+def query_permutation(p, Q, Kc, qidx=None, ws=None):
+    if qidx is None:
+        qidx = torch.empty((p.batch, p.h_q, p.n), dtype=torch.int32, device=Q.device)
+    ws, wp, wn = _ws_args(p, STAGE_QUERY_PERMUTE, ws)
+    _check(load_library().pbs_query_permutation(ctypes.byref(p), _ptr(Q), _ptr(Kc), _ptr(qidx), wp, wn, _stream()),
+           "pbs_query_permutation")
+    return qidx
 
 
 def block_mask(p, Qp, Kp, mask_bits=None, row_cnt=None, col_idx=None, ws=None):

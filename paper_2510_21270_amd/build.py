@@ -13,7 +13,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(CSRC, "_build")
 LIB = os.path.join(HERE, "libpbs.so")
 SOURCES = ["status.hip", "key_scores.hip", "permute.hip", "block_mask.hip", "attn_fwd.hip", "attn_wide.hip",
-           "mfma_probe.hip", "coverage.hip"]
+           "mfma_probe.hip", "coverage.hip", "query_permute.hip"]
 HEADERS = ["pbs_device.h", "pbs_host.h", os.path.join("..", "..", "include", "pbs.h")]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function", "-Wno-array-bounds",
          # packed fp32 instructions are kept off on the test machines

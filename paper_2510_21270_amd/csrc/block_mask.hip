@@ -355,6 +355,17 @@ pbs_status launch_pool_keys(const pbs_problem *p, const Geo &g, const void *Kp, 
                   g.T, kbar_stride(g.T));
 }
 
+// Block means of the keys K, row-major ([kv head][block][feature] fp64): the centroids of the query permutation.
+pbs_status launch_pool_keys_rowmajor(const pbs_problem *p, const Geo &g, const void *K, double *Kbar, hipStream_t s)
+{
+    const int nk = g.batch * g.h_kv;
+    if (p->dtype == PBS_BF16)
+        return launch((pool_kernel<bf16_t, false>), dim3(g.T, nk), dim3(256), 0, s, (const bf16_t *)K, Kbar, g.n, g.d,
+                      g.block, g.T, g.T);
+    return launch((pool_kernel<float, false>), dim3(g.T, nk), dim3(256), 0, s, (const float *)K, Kbar, g.n, g.d, g.block,
+                  g.T, g.T);
+}
+
 size_t ws_block_mask(const pbs_problem *p)
 {
     const Geo g = make_geo(p);

@@ -16,6 +16,8 @@ namespace pbs {
 // grid = (G + 1, batch*h_kv); workgroup G writes the identity for the unpermuted tail.
 // ---------------------------------------------------------------------------------------------
 // identity != NULL: the positions 0 .. n-1 are written there as well (the kidx of a token-order copy).
+// INT_KEYS: `scores` holds int32 keys instead, sorted ascending (equal keys in ascending position).
+template <bool INT_KEYS>
 __global__ __launch_bounds__(1024) void segment_argsort_kernel(const float *__restrict__ scores,
                                                                int32_t *__restrict__ kidx,
                                                                int32_t *__restrict__ identity, int n, int segment,
@@ -36,10 +38,15 @@ __global__ __launch_bounds__(1024) void segment_argsort_kernel(const float *__re
     for (int t = threadIdx.x; t < p2; t += blockDim.x) {
         uint64_t key = ~0ull;
         if (t < segment) {
-            float f = s[t] + 0.0f;
-            uint32_t u = __float_as_uint(f);
-            u = (u & 0x80000000u) ? ~u : (u | 0x80000000u);   // ascending in u == ascending in f
-            key = ((uint64_t)(~u) << 32) | (uint32_t)t;
+            if (INT_KEYS) {
+                const uint32_t u = (uint32_t)reinterpret_cast<const int32_t *>(s)[t] ^ 0x80000000u;   // signed order
+                key = ((uint64_t)u << 32) | (uint32_t)t;
+            } else {
+                float f = s[t] + 0.0f;
+                uint32_t u = __float_as_uint(f);
+                u = (u & 0x80000000u) ? ~u : (u | 0x80000000u);   // ascending in u == ascending in f
+                key = ((uint64_t)(~u) << 32) | (uint32_t)t;
+            }
         }
         keys[t] = key;
     }
@@ -315,6 +322,16 @@ static dim3 move_grid(int n, int cpr, int nbh)
     return dim3((unsigned)bx, (unsigned)nbh);
 }
 
+// idx[head][g*S + t] = position of the query with the t-th smallest (key, position) of segment g; the tail keeps its place.
+pbs_status launch_segment_sort_by_int_key(const Geo &g, int heads, const int32_t *keys, int32_t *idx, hipStream_t s)
+{
+    int p2 = 1;
+    while (p2 < g.segment) p2 <<= 1;
+    const int threads = p2 / 2 < 64 ? 64 : (p2 / 2 > 1024 ? 1024 : p2 / 2);
+    return launch(segment_argsort_kernel<true>, dim3(g.G + 1, heads), dim3(threads), (size_t)p2 * sizeof(uint64_t), s,
+                  reinterpret_cast<const float *>(keys), idx, (int32_t *)nullptr, g.n, g.segment, g.G, p2);
+}
+
 size_t ws_block_mask(const pbs_problem *p);
 pbs_status launch_pool_keys(const pbs_problem *p, const Geo &g, const void *Kp, double *KbarT, hipStream_t s);
 
@@ -344,7 +361,7 @@ extern "C" pbs_status pbs_segment_permute(const pbs_problem *p, const float *sco
         int p2 = 1;
         while (p2 < g.segment) p2 <<= 1;
         const int threads = p2 / 2 < 64 ? 64 : (p2 / 2 > 1024 ? 1024 : p2 / 2);
-        st = launch(segment_argsort_kernel, dim3(g.G + 1, nbh), dim3(threads), (size_t)p2 * sizeof(uint64_t), s,
+        st = launch(segment_argsort_kernel<false>, dim3(g.G + 1, nbh), dim3(threads), (size_t)p2 * sizeof(uint64_t), s,
                            scores, kidx, kidx_tok, g.n, g.segment, g.G, p2);
     } else {
         const size_t total = (size_t)nbh * g.n;

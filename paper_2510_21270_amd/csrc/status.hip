@@ -5,6 +5,7 @@ namespace pbs {
 size_t ws_key_scores(const pbs_problem *p);
 size_t ws_block_mask(const pbs_problem *p);
 size_t ws_attn_fwd(const pbs_problem *p);
+size_t ws_query_permute(const pbs_problem *p);
 }  // namespace pbs
 
 extern "C" const char *pbs_status_string(pbs_status st)
@@ -29,6 +30,7 @@ extern "C" size_t pbs_workspace_bytes(const pbs_problem *p, int stage)
     case PBS_STAGE_KEY_SCORES: return pbs::ws_key_scores(p);
     case PBS_STAGE_BLOCK_MASK: return pbs::ws_block_mask(p);
     case PBS_STAGE_ATTN_FWD: return pbs::ws_attn_fwd(p);
+    case PBS_STAGE_QUERY_PERMUTE: return pbs::ws_query_permute(p);
     default: return 0;
     }
 }

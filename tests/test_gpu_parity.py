@@ -160,6 +160,37 @@ def test_coverage_of_the_selected_blocks(lib, oracle, name, sigma):
     assert want.mean() > 0.5                            # tau >= 0.7 on pooled scores keeps most of the true mass here
 
 
+@pytest.mark.parametrize("on_permuted_keys", [False, True])
+@pytest.mark.parametrize("name", CASES + ["bf16_even"])
+def test_key_aware_query_permutation(lib, oracle, oracle_variants, name, on_permuted_keys):
+    # the ablation of Section "Design Choice: Why Permute Keys but not Queries?": sigma is an argmax followed by a
+    # stable sort, all in fp64 with the plain operation order on both sides, so the indices must agree bit for bit;
+    # then the whole path with this sigma doing real work (Q' gathered, mask on Q', attention with qidx, O scattered)
+    w, res = _oracle_run(oracle, name, False)
+    p = make_problem(w)
+    keys_h = res["Kp"] if on_permuted_keys else np.asarray(w.K, dtype=np.float32)
+    want = oracle_variants.query_permutation(w.Q, keys_h, w.block, w.segment)
+    Q = to_dev(w.Q, w.dtype)
+    qidx = pbs.query_permutation(p, Q, to_dev(keys_h, w.dtype))
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(qidx.cpu().numpy(), want)
+    if not on_permuted_keys:
+        return
+    full = (w.n // w.segment) * w.segment
+    if full:
+        assert not np.array_equal(want[0, 0, :full], np.arange(full))          # it does reorder something
+    ref = oracle.pipeline(w.Q, w.K, w.V, w.block, w.segment, w.tau, flags=w.flags, qidx=want)
+    Qp = pbs.permute_rows(p, Q, qidx)
+    np.testing.assert_array_equal(to_host(Qp), ref["Qp"].astype(np.float64))
+    Kp, Vt = to_dev(ref["Kp"], w.dtype), to_dev(vt_layout(ref["Vp"], w.block), w.dtype)
+    bits, cnt, cols = pbs.block_mask(p, Qp, Kp)
+    np.testing.assert_array_equal(mask_from_bits(bits, w.T), ref["mask"])
+    Op = pbs.attn_fwd(p, Qp, Kp, Vt, qidx, i32_dev(ref["kidx"]), cnt, cols)
+    O = pbs.unpermute(p, Op, qidx)
+    torch.cuda.synchronize()
+    check_close(to_host(O), ref["O"], w.dtype, name + " O with the key-aware sigma")
+
+
 @pytest.mark.parametrize("proxy", ["last", "rows", "rows_few", "avg"])
 @pytest.mark.parametrize("name", ["c1", "bf16_b128", "bf16_b64", "bf16_d64", "bf16_r7"])
 def test_key_scores_from_other_proxies(lib, oracle, oracle_variants, name, proxy):
