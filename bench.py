@@ -296,8 +296,20 @@ def main():
                 "layer_speedup_of_the_sparse_path": ms_dense / ms_per_step}
             del rc_dense, ci_dense
         # what the matrix units sustain on their own, with operand bits that cost no / realistic switching power
-        extras["mfma_alone_tflops"] = {"zero_operands": pbs.mfma_rate_probe(False),
-                                       "random_operands": pbs.mfma_rate_probe(True)}
+        zero_rate, zero_mhz = pbs.mfma_rate_probe(False)
+        rand_rate, rand_mhz = pbs.mfma_rate_probe(True)
+        extras["mfma_alone_tflops"] = {"zero_operands": zero_rate, "random_operands": rand_rate}
+        extras["shader_clock_mhz"] = {"mfma_alone_zero_operands": zero_mhz, "mfma_alone_random_operands": rand_mhz}
+        if not given:
+            # the clock pbs_attn_fwd runs at: one watching wave on a second stream beside two attention launches
+            def two_attention_launches():
+                for _ in range(2):
+                    pbs.attn_fwd(p, Q, pipe.Kp, pipe.Vt, None, pipe.kidx, pipe.row_cnt, pipe.col_idx, pipe.Op,
+                                 ws=pipe.ws4)
+            mhz, watched_us = pbs.shader_clock_beside(two_attention_launches, micros=20000,
+                                                      delay_s=min(0.02, stage_ms["attn_fwd"] * 0.3e-3))
+            if watched_us < 1.2e3 * stage_ms["attn_fwd"]:      # the watch ended inside the launches
+                extras["shader_clock_mhz"]["pbs_attn_fwd"] = mhz
 
     cnt = (row_cnt if given else pipe.row_cnt).cpu().numpy().astype(np.int64)
     visited = int(cnt.sum())                           # blocks the masks list

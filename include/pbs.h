@@ -274,16 +274,24 @@ pbs_status pbs_mass_covered(const pbs_problem *p, const float *lse_listed, const
                             void *stream);
 
 /*
- * Measurement aid, not a step of Algorithm 1: launches a kernel that does nothing but bf16 matrix instructions
- * (one wave per SIMD on 256 compute units, operands in registers) for `iters` rounds of 32 instructions, with all-zero
- * operands (random_operands = 0) or pseudo-random ones.  The caller times the launch on `stream`; *flop (host memory)
- * receives the number of floating-point operations it performs.  The clock of the chip under matrix load depends on
- * the operand bits, so the rate with random operands is the matrix rate a kernel working on real data can approach.
- *   sink: device memory, sink_floats >= 65536 float32, overwritten.  iters in [1, 2^22].
- * Errors: PBS_ERR_NULL, PBS_ERR_SHAPE (iters or sink_floats out of range), PBS_ERR_HIP.
+ * Measurement aids, not steps of Algorithm 1.
+ * pbs_mfma_rate_probe launches a kernel that does nothing but bf16 matrix instructions (four waves per SIMD on 256
+ * compute units, operands in registers, no other instruction in the loop) for `iters` rounds of 32 instructions, with
+ * all-zero operands (random_operands = 0) or pseudo-random ones.  The caller times the launch on `stream`; *flop (host
+ * memory) receives the number of floating-point operations it performs.  The instruction rate per clock is the same
+ * in both cases; the clock the chip grants under matrix load depends on the operand bits, so the rate with random
+ * operands is the matrix rate a kernel working on real data can approach.
+ *   sink: device memory, sink_floats >= 262144 float32, overwritten; afterwards sink[0] = shader clock in MHz that one
+ *   wave of the launch saw, sink[1] = that wave's clocks per matrix instruction (four waves share a SIMD: 4 x 32 in a
+ *   long run).  iters in [1, 2^22].
+ * pbs_shader_clock_meter launches one wave that compares the shader-clock counter with the constant 100 MHz counter
+ * for about `micros` microseconds (1 .. 2 000 000) and writes out[0] = shader clock in MHz, out[1] = microseconds
+ * watched (device memory, 2 floats).  Launched on a second stream beside another kernel it reports that kernel's clock.
+ * Errors: PBS_ERR_NULL, PBS_ERR_SHAPE (a size or count out of range), PBS_ERR_HIP.
  */
 pbs_status pbs_mfma_rate_probe(int random_operands, int iters, float *sink, size_t sink_floats, double *flop,
                                void *stream);
+pbs_status pbs_shader_clock_meter(float *out, int micros, void *stream);
 
 #ifdef __cplusplus
 }

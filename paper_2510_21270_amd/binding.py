@@ -21,7 +21,7 @@ FLAG_FORCE_FIRST_BLOCK, FLAG_TOKEN_ORDER_COPY, FLAG_RUNNING_MAX_ONLY, FLAG_KBAR_
 EXPORTS = ["pbs_status_string", "pbs_validate", "pbs_workspace_bytes", "pbs_vt_bytes", "pbs_key_scores",
            "pbs_segment_permute", "pbs_permute_rows", "pbs_block_mask", "pbs_attn_fwd", "pbs_unpermute",
            "pbs_mfma_rate_probe", "pbs_key_scores_static", "pbs_key_scores_static_scratch_bytes", "pbs_admitted_lists",
-           "pbs_mass_covered", "pbs_key_scores_proxy", "pbs_query_permutation"]
+           "pbs_mass_covered", "pbs_key_scores_proxy", "pbs_query_permutation", "pbs_shader_clock_meter"]
 
 
 class PbsError(RuntimeError):
@@ -65,6 +65,7 @@ def load_library():
         lib.pbs_admitted_lists.argtypes = [P, V, V, V]
         lib.pbs_mass_covered.argtypes = [P, V, V, V, V]
         lib.pbs_mfma_rate_probe.argtypes = [ctypes.c_int, ctypes.c_int, V, Z, ctypes.POINTER(ctypes.c_double), V]
+        lib.pbs_shader_clock_meter.argtypes = [V, ctypes.c_int, V]
         _lib = lib
     return _lib
 
@@ -274,10 +275,11 @@ def mass_covered(p, lse_listed, lse_admitted, covered=None):
 
 
 def mfma_rate_probe(random_operands, iters=20000, reps=3):
-    """TFLOP/s of the matrix units alone (best of `reps` launches timed with events on the current stream)."""
-    sink = torch.empty(65536, dtype=torch.float32, device="cuda")
+    """(TFLOP/s, shader clock in MHz) of the matrix units alone: best of `reps` launches timed with events on the
+    current stream, and the clock one wave of that launch saw."""
+    sink = torch.empty(262144, dtype=torch.float32, device="cuda")
     flop = ctypes.c_double(0.0)
-    best = 0.0
+    best, mhz = 0.0, 0.0
     for _ in range(reps + 1):                              # the first launch warms up
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
@@ -285,8 +287,26 @@ def mfma_rate_probe(random_operands, iters=20000, reps=3):
                                                   ctypes.byref(flop), _stream()), "pbs_mfma_rate_probe")
         e1.record()
         e1.synchronize()
-        best = max(best, flop.value / (e0.elapsed_time(e1) * 1e-3) / 1e12)
-    return best
+        rate = flop.value / (e0.elapsed_time(e1) * 1e-3) / 1e12
+        if rate > best:
+            best, mhz = rate, float(sink[0])
+    return best, mhz
+
+
+def shader_clock_beside(fn, micros=20000, delay_s=0.02):
+    """Shader clock in MHz while fn()'s kernels run on the current stream: fn() is enqueued, then, after delay_s, one
+    watching wave on a second stream (default priority) for `micros` microseconds.  fn's work must outlast both."""
+    import time
+    out = torch.zeros(2, dtype=torch.float32, device="cuda")
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    fn()
+    time.sleep(delay_s)
+    with torch.cuda.stream(side):
+        _check(load_library().pbs_shader_clock_meter(_ptr(out), int(micros), ctypes.c_void_p(side.cuda_stream)),
+               "pbs_shader_clock_meter")
+    torch.cuda.synchronize()
+    return float(out[0]), float(out[1])
 
 
 class Pipeline:

@@ -88,10 +88,12 @@ def test_null_pointers_are_rejected_before_any_launch(lib):
     assert lib.pbs_unpermute(ref, ctypes.c_void_p(4096 + 4), None, fake, None) == 2
     # the measurement aid checks its arguments before launching as well
     flop = ctypes.c_double(0.0)
-    assert lib.pbs_mfma_rate_probe(1, 10, None, 65536, ctypes.byref(flop), None) == 1
-    assert lib.pbs_mfma_rate_probe(1, 10, fake, 65536, None, None) == 1
-    assert lib.pbs_mfma_rate_probe(1, 0, fake, 65536, ctypes.byref(flop), None) == 2
-    assert lib.pbs_mfma_rate_probe(1, 10, fake, 65535, ctypes.byref(flop), None) == 2
+    assert lib.pbs_mfma_rate_probe(1, 10, None, 262144, ctypes.byref(flop), None) == 1
+    assert lib.pbs_mfma_rate_probe(1, 10, fake, 262144, None, None) == 1
+    assert lib.pbs_mfma_rate_probe(1, 0, fake, 262144, ctypes.byref(flop), None) == 2
+    assert lib.pbs_mfma_rate_probe(1, 10, fake, 262143, ctypes.byref(flop), None) == 2
+    assert lib.pbs_shader_clock_meter(None, 100, None) == 1
+    assert lib.pbs_shader_clock_meter(fake, 0, None) == 2
     # invalid problem wins over everything
     bad = _p(h_q=30)
     assert lib.pbs_attn_fwd(ctypes.byref(bad), None, None, None, None, None, None, None, None, None, None, 0, None) == 2

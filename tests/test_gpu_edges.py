@@ -218,18 +218,25 @@ def test_rescaling_kernel_alone_serves_block_128(oracle):
 
 
 def test_matrix_rate_probe_runs_and_counts_its_work():
-    # measurement aid of bench.py: 512 workgroups x 2 waves x iters x 32 instructions of 32 x 32 x 16 multiply-adds
+    # measurement aid of bench.py: 1024 workgroups x 4 waves x iters x 32 instructions of 32 x 32 x 16 multiply-adds
     import ctypes
     lib = pbs.load_library()
-    sink = torch.empty(65536, dtype=torch.float32, device="cuda")
+    sink = torch.empty(262144, dtype=torch.float32, device="cuda")
     flop = ctypes.c_double(0.0)
     for random_operands in (0, 1):
         assert lib.pbs_mfma_rate_probe(random_operands, 100, sink.data_ptr(), sink.numel(), ctypes.byref(flop), None) == 0
         torch.cuda.synchronize()
-        assert flop.value == 512 * 2 * 100 * 32 * 2.0 * 32 * 32 * 16
+        assert flop.value == 1024 * 4 * 100 * 32 * 2.0 * 32 * 32 * 16
+        assert 500.0 < float(sink[0]) < 3000.0             # the shader clock one wave saw, MHz
+        assert 31.0 < float(sink[1]) < 160.0               # 32 clocks per instruction, up to four waves on a SIMD
         assert torch.isfinite(sink).all()
     assert (sink != 0).any()                           # random operands leave non-zero accumulators
-    assert pbs.mfma_rate_probe(True, iters=2000, reps=1) > 100.0
+    rate, mhz = pbs.mfma_rate_probe(True, iters=2000, reps=1)
+    assert rate > 100.0 and 500.0 < mhz < 3000.0
+    # the clock meter beside a kernel that keeps the GPU busy for a while
+    mhz2, watched = pbs.shader_clock_beside(lambda: lib.pbs_mfma_rate_probe(1, 40000, sink.data_ptr(), sink.numel(),
+                                                                            ctypes.byref(flop), None), micros=5000)
+    assert 500.0 < mhz2 < 3000.0 and watched >= 4900.0
 
 
 @pytest.mark.parametrize("extra_flags", [0, pbs.FLAG_TOKEN_ORDER_COPY])
