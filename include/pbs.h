@@ -78,9 +78,17 @@ typedef enum { PBS_F32 = 0, PBS_BF16 = 1 } pbs_dtype;
  *   pass, which keeps a fixed softmax reference per query.  Same result up to rounding; slower.
  * PBS_FLAG_KBAR_IN_WS: the workspace given to pbs_block_mask already holds the block means of Kp, left there by
  *   the pbs_segment_permute call that wrote this Kp (see its `ws`); pbs_block_mask then does not read Kp at all.
+ * PBS_FLAG_INDEX_REMAP: index remapping as the appendix "Memory Overhead" sketches it (the attention kernel retrieves
+ *   the keys from the original tensor through the permuted indices): no K' exists.  pbs_segment_permute writes kidx
+ *   and Vt only (its Kp argument is ignored and may be NULL; with a workspace it still leaves the block means of the
+ *   permuted keys there), pbs_block_mask must then be given PBS_FLAG_KBAR_IN_WS as well, and pbs_attn_fwd takes the
+ *   caller's K in place of Kp and gathers the rows kidx[slot] while it stages its tiles.  bf16, d = 128, block 64 or
+ *   128 only (PBS_ERR_UNSUPPORTED otherwise, and together with PBS_FLAG_TOKEN_ORDER_COPY); same results as with a
+ *   materialised K', bit for bit against PBS_FLAG_RUNNING_MAX_ONLY (it runs on that kernel).  V' stays materialised
+ *   as Vt: the second matrix product needs it feature-major.
  */
 enum { PBS_FLAG_FORCE_FIRST_BLOCK = 1u, PBS_FLAG_TOKEN_ORDER_COPY = 2u, PBS_FLAG_RUNNING_MAX_ONLY = 4u,
-       PBS_FLAG_KBAR_IN_WS = 8u };
+       PBS_FLAG_KBAR_IN_WS = 8u, PBS_FLAG_INDEX_REMAP = 16u };
 
 typedef enum {
     PBS_STAGE_KEY_SCORES = 1,

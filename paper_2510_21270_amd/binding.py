@@ -16,7 +16,7 @@ _lib = None
 PBS_F32, PBS_BF16 = 0, 1
 STAGE_KEY_SCORES, STAGE_SEGMENT_PERMUTE, STAGE_BLOCK_MASK, STAGE_ATTN_FWD, STAGE_UNPERMUTE = 1, 2, 3, 4, 5
 STAGE_QUERY_PERMUTE = 6
-FLAG_FORCE_FIRST_BLOCK, FLAG_TOKEN_ORDER_COPY, FLAG_RUNNING_MAX_ONLY, FLAG_KBAR_IN_WS = 1, 2, 4, 8
+FLAG_FORCE_FIRST_BLOCK, FLAG_TOKEN_ORDER_COPY, FLAG_RUNNING_MAX_ONLY, FLAG_KBAR_IN_WS, FLAG_INDEX_REMAP = 1, 2, 4, 8, 16
 
 EXPORTS = ["pbs_status_string", "pbs_validate", "pbs_workspace_bytes", "pbs_vt_bytes", "pbs_key_scores",
            "pbs_segment_permute", "pbs_permute_rows", "pbs_block_mask", "pbs_attn_fwd", "pbs_unpermute",
@@ -194,7 +194,7 @@ def segment_permute(p, scores, K, V, kidx=None, Kp=None, Vt=None, indices_only=F
     if kidx is None:
         kidx = alloc_kidx(p, dev)
     if not indices_only:
-        if Kp is None:
+        if Kp is None and not (p.flags & FLAG_INDEX_REMAP):
             Kp = alloc_kp(p, dev)
         if Vt is None:
             Vt = alloc_vt(p, dev)

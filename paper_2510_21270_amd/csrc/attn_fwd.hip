@@ -110,18 +110,45 @@ __device__ inline LaneOffsets<WAVES, KT> lane_offsets(int wave, int lane)
     return o;
 }
 
+// Index remapping (appendix "Memory Overhead": the kernel retrieves the keys directly from the original tensor through
+// the permuted indices): the rows of a K' sub-tile are rows kidx[slot] of the caller's K.  A lane needs the index of
+// the one row it moves in each of its load chunks; KeyRows holds them for one sub-tile, fetched one sub-tile ahead of
+// the loads that use them (they arrive under the multiplication of the sub-tile in between).
+template <int WAVES, int KT>
+struct KeyRows {
+    int row[(SubTile<KT>::kKLoads + WAVES - 1) / WAVES];
+};
+
+// kidx entries of the rows this lane moves for the sub-tile at `half` of block j (slots past n read as 0: row 0,
+// whose scores are discarded by the slot test like those of any slot past n)
 template <int BLOCK, int WAVES, int KT>
+__device__ inline void fetch_key_rows(KeyRows<WAVES, KT> &kr, const TileBuffers &buf, const LaneOffsets<WAVES, KT> &off,
+                                      int j, int half)
+{
+    const int slot0 = j * BLOCK + half * KT;
+#pragma unroll
+    for (int y = 0; y < (SubTile<KT>::kKLoads + WAVES - 1) / WAVES; ++y)
+        kr.row[y] = __builtin_amdgcn_raw_buffer_load_b32(buf.pos, (off.k[y] >> 8) * 4, slot0 * 4, 0);
+}
+
+template <int BLOCK, int WAVES, int KT, bool REMAP>
 __device__ inline void issue_subtile(unsigned char *kbuf, unsigned char *vbuf, int *kpos, const TileBuffers &buf,
-                                     const LaneOffsets<WAVES, KT> &off, int j, int half, bool masked, int wave, int lane)
+                                     const LaneOffsets<WAVES, KT> &off, const KeyRows<WAVES, KT> &kr, int j, int half,
+                                     bool masked, int wave, int lane)
 {
     constexpr int kKLoads = SubTile<KT>::kKLoads, kVLoads = SubTile<KT>::kVLoads;
     const int slot0 = j * BLOCK + half * KT;               // uniform
     // full rounds are unconditional; only the last, partial round of chunks tests the wave index
 #pragma unroll
     for (int y = 0; y < (kKLoads + WAVES - 1) / WAVES; ++y)
-        if (y < kKLoads / WAVES || wave < kKLoads % WAVES)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(buf.k, (lptr_t)(kbuf + (wave + WAVES * y) * 1024), 16, off.k[y],
-                                                     slot0 * 256, 0, 0);
+        if (y < kKLoads / WAVES || wave < kKLoads % WAVES) {
+            if (REMAP)                                     // buf.k is the caller's K: row kidx[slot], same 16-byte piece
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(buf.k, (lptr_t)(kbuf + (wave + WAVES * y) * 1024), 16,
+                                                         (uint32_t)kr.row[y] * 256u + (off.k[y] & 255u), 0, 0, 0);
+            else
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(buf.k, (lptr_t)(kbuf + (wave + WAVES * y) * 1024), 16, off.k[y],
+                                                         slot0 * 256, 0, 0);
+        }
 #pragma unroll
     for (int y = 0; y < (kVLoads + WAVES - 1) / WAVES; ++y)
         if (y < kVLoads / WAVES || wave < kVLoads % WAVES)
@@ -314,7 +341,8 @@ __device__ inline void compute_subtile(AttnState<NT> &st, const unsigned char *k
     }
 }
 
-template <int BLOCK, int WAVES, int KT>
+// REMAP: Kp is the caller's K in token order and the K' sub-tiles are gathered from it through kidx (index remapping).
+template <int BLOCK, int WAVES, int KT, bool REMAP = false>
 __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_mfma_kernel(
     const bf16_t *__restrict__ Qp, const bf16_t *__restrict__ Kp, const bf16_t *__restrict__ Vt,
     const int32_t *__restrict__ qidx, const int32_t *__restrict__ kidx, const int32_t *__restrict__ row_cnt,
@@ -399,18 +427,31 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 2
         __syncthreads();
         const int total = len * SUBS;
         auto block_at = [&](int s) -> int { return __builtin_amdgcn_readfirstlane(jl[s / SUBS]); };
+        // with index remapping: the key rows of the sub-tile whose loads are issued next
+        KeyRows<WAVES, KT> kr;
+        auto fetch_rows = [&](int s) {
+            if (REMAP && s < total) {
+                const int js = block_at(s);
+                if (js >= 0) fetch_key_rows<BLOCK, WAVES, KT>(kr, buf, off, js, s % SUBS);
+            }
+        };
+        fetch_rows(0);
         {
             const int j0 = block_at(0);
-            if (j0 >= 0) issue_subtile<BLOCK, WAVES, KT>(kbuf0, vbuf0, kpos0, buf, off, j0, 0, j0 >= jmask, wave, lane);
+            if (j0 >= 0)
+                issue_subtile<BLOCK, WAVES, KT, REMAP>(kbuf0, vbuf0, kpos0, buf, off, kr, j0, 0, j0 >= jmask, wave, lane);
+            fetch_rows(1);
         }
         for (int s = 0; s < total; s += 2) {
-            sync_tiles();                  // sub-tile s has landed in buffer 0; buffer 1 is free again
+            sync_tiles();                  // sub-tile s has landed in buffer 0; buffer 1 is free again (and the key
+                                           // rows of sub-tile s + 1 have arrived: the wait covers every load)
             if (s + 1 < total) {
                 const int j1 = block_at(s + 1);
                 if (j1 >= 0)
-                    issue_subtile<BLOCK, WAVES, KT>(kbuf1, vbuf1, kpos1, buf, off, j1, (s + 1) % SUBS, j1 >= jmask, wave,
-                                                lane);
+                    issue_subtile<BLOCK, WAVES, KT, REMAP>(kbuf1, vbuf1, kpos1, buf, off, kr, j1, (s + 1) % SUBS,
+                                                           j1 >= jmask, wave, lane);
             }
+            fetch_rows(s + 2);
             {
                 const int j = block_at(s);
                 if (j >= 0)
@@ -422,9 +463,10 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 2
             if (s + 2 < total) {
                 const int j2 = block_at(s + 2);
                 if (j2 >= 0)
-                    issue_subtile<BLOCK, WAVES, KT>(kbuf0, vbuf0, kpos0, buf, off, j2, (s + 2) % SUBS, j2 >= jmask, wave,
-                                                lane);
+                    issue_subtile<BLOCK, WAVES, KT, REMAP>(kbuf0, vbuf0, kpos0, buf, off, kr, j2, (s + 2) % SUBS,
+                                                           j2 >= jmask, wave, lane);
             }
+            fetch_rows(s + 3);
             {
                 const int j = block_at(s + 1);
                 if (j >= 0)
@@ -593,7 +635,17 @@ extern "C" pbs_status pbs_attn_fwd(const pbs_problem *p, const void *Qp, const v
     if (p->dtype == PBS_BF16 && p->d == 128 && (p->block == 128 || p->block == 64)) {
         const int ncoh = g.batch * g.h_kv * ((g.r * g.T + kCohort - 1) / kCohort);
         const dim3 mgrid((unsigned)(((ncoh + kXcds - 1) / kXcds) * kCohort * kXcds));
-        const bool narrow_only = (p->flags & PBS_FLAG_RUNNING_MAX_ONLY) != 0;
+        const bool remap = (p->flags & PBS_FLAG_INDEX_REMAP) != 0;     // Kp is the caller's K
+        const bool narrow_only = (p->flags & PBS_FLAG_RUNNING_MAX_ONLY) != 0 || remap;
+        if (remap) {
+            if (p->block == 128)
+                return launch((attn_mfma_kernel<128, 4, 64, true>), mgrid, dim3(256), 0, s, (const bf16_t *)Qp,
+                              (const bf16_t *)Kp, (const bf16_t *)Vt, qidx, kidx, row_cnt, col_idx, (bf16_t *)Op, lse,
+                              (const int32_t *)nullptr, g);
+            return launch((attn_mfma_kernel<64, 2, 32, true>), mgrid, dim3(128), 0, s, (const bf16_t *)Qp,
+                          (const bf16_t *)Kp, (const bf16_t *)Vt, qidx, kidx, row_cnt, col_idx, (bf16_t *)Op, lse,
+                          (const int32_t *)nullptr, g);
+        }
         if (p->block == 128) {
             // first pass: every query block with a fixed softmax reference; second pass: the flagged blocks (none
             // on ordinary inputs, then each workgroup of the second launch leaves at once) with the rescaling kernel
@@ -618,6 +670,7 @@ extern "C" pbs_status pbs_attn_fwd(const pbs_problem *p, const void *Qp, const v
         }
         return st;
     }
+    if (p->flags & PBS_FLAG_INDEX_REMAP) return PBS_ERR_UNSUPPORTED;   // only the matrix-core kernels remap
     if (p->dtype == PBS_BF16)
         return p->d == 128 ? launch_vector<bf16_t, 128>(g, Qp, Kp, Vt, qidx, kidx, row_cnt, col_idx, Op, lse, s)
                            : launch_vector<bf16_t, 64>(g, Qp, Kp, Vt, qidx, kidx, row_cnt, col_idx, Op, lse, s);

@@ -145,7 +145,8 @@ __global__ __launch_bounds__(256) void move_rows_kernel(const uintx4 *__restrict
 // A workgroup owns whole key blocks (its range is a multiple of block * cpr chunks, and a block is a whole number of
 // 1024-chunk batches), a thread always meets the same 16-byte column group, so it adds up its rows' eight features in
 // fp64 registers while the rows pass through (sums of bf16 values are exact in fp64 in any order), and at the end of
-// every block the 256 / cpr row slots of a column meet in LDS.
+// every block the 256 / cpr row slots of a column meet in LDS.  dst == NULL: only the block means are produced (index
+// remapping: the attention kernel gathers the rows itself and no K' is written).
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void gather_pool_kernel(const uintx4 *__restrict__ src,
                                                           const int32_t *__restrict__ idx, uintx4 *__restrict__ dst,
@@ -184,10 +185,12 @@ __global__ __launch_bounds__(256) void gather_pool_kernel(const uintx4 *__restri
             v[u] = uintx4{0u, 0u, 0u, 0u};
             if (other[u] >= 0 && other[u] < n) v[u] = hsrc[((uint32_t)other[u] << cpr_log2) + (c & cmask)];
         }
+        if (dst) {
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const uint32_t c = base + threadIdx.x + u * 256;
-            if (c < end) hdst[c] = v[u];
+            for (int u = 0; u < U; ++u) {
+                const uint32_t c = base + threadIdx.x + u * 256;
+                if (c < end) hdst[c] = v[u];
+            }
         }
         if (plain) continue;                                  // uniform: the token-order copy is not pooled
 #pragma unroll
@@ -346,11 +349,18 @@ extern "C" pbs_status pbs_segment_permute(const pbs_problem *p, const float *sco
     pbs_status st = validate(p);
     if (st != PBS_OK) return st;
     if (!kidx) return PBS_ERR_NULL;
+    const bool remap = (p->flags & PBS_FLAG_INDEX_REMAP) != 0;    // no K' is written: Kp is ignored and may be NULL
+    if (remap) {
+        if (p->flags & PBS_FLAG_TOKEN_ORDER_COPY) return PBS_ERR_UNSUPPORTED;
+        if (Vt && !Kp) Kp = Vt;                                   // "both or none" below is about Vt alone then
+        if (!Vt) Kp = nullptr;
+    }
     if ((Kp == nullptr) != (Vt == nullptr)) return PBS_ERR_NULL;
     if (ws && Kp && ((reinterpret_cast<uintptr_t>(ws) & (kWsAlign - 1)) != 0 || ws_bytes < ws_block_mask(p)))
         return PBS_ERR_WORKSPACE;
     if (Kp && (!K || !V)) return PBS_ERR_NULL;
     if (Kp && (!aligned16(K) || !aligned16(V) || !aligned16(Kp) || !aligned16(Vt))) return PBS_ERR_SHAPE;
+    void *kdst = remap ? nullptr : Kp;
     const Geo g = make_geo(p);
     hipStream_t s = (hipStream_t)stream;
     const int nbh = g.batch * g.h_kv;
@@ -378,12 +388,13 @@ extern "C" pbs_status pbs_segment_permute(const pbs_problem *p, const float *sco
     // block is a whole number of its 1024-chunk batches (2-byte storage), by the pooling kernel otherwise
     double *kbarT = reinterpret_cast<double *>(ws);
     const bool pool_on_the_way = kbarT && p->dtype == PBS_BF16 && (g.block * cpr) % 1024 == 0;
+    if (remap && kbarT && !pool_on_the_way) return PBS_ERR_UNSUPPORTED;   // means without K' only from the gather kernel
     if (pool_on_the_way)
-        st = launch(gather_pool_kernel, mg, dim3(256), 0, s, (const uintx4 *)K, (const int32_t *)kidx, (uintx4 *)Kp, g.n,
-                    ilog2(cpr), token_copy ? tok_rows * cpr : (size_t)0, kbarT, g.block, kbar_stride(g.T));
-    else
+        st = launch(gather_pool_kernel, mg, dim3(256), 0, s, (const uintx4 *)K, (const int32_t *)kidx, (uintx4 *)kdst,
+                    g.n, ilog2(cpr), token_copy ? tok_rows * cpr : (size_t)0, kbarT, g.block, kbar_stride(g.T));
+    else if (kdst)
         st = launch(move_rows_kernel<false>, mg, dim3(256), 0, s, (const uintx4 *)K, (const int32_t *)kidx,
-                    (uintx4 *)Kp, g.n, ilog2(cpr), token_copy ? tok_rows * cpr : (size_t)0);
+                    (uintx4 *)kdst, g.n, ilog2(cpr), token_copy ? tok_rows * cpr : (size_t)0);
     if (st != PBS_OK) return st;
     if (kbarT && !pool_on_the_way && (st = launch_pool_keys(p, g, Kp, kbarT, s)) != PBS_OK) return st;
     const dim3 vg(token_copy ? 2 * g.T : g.T, nbh);

@@ -160,6 +160,44 @@ def test_coverage_of_the_selected_blocks(lib, oracle, name, sigma):
     assert want.mean() > 0.5                            # tau >= 0.7 on pooled scores keeps most of the true mass here
 
 
+@pytest.mark.parametrize("sigma", [False, True])
+@pytest.mark.parametrize("name", ["bf16_b128", "bf16_b64", "bf16_even", "bf16_r7"])
+def test_index_remapped_attention_reads_the_original_keys(lib, oracle, name, sigma):
+    # PBS_FLAG_INDEX_REMAP (appendix "Memory Overhead"): no K' is materialised; the permutation stage writes kidx, Vt
+    # and the block means of the permuted keys, selection runs from those means, and the attention kernel gathers its
+    # K tiles from the caller's K through kidx.  Everything must match the oracle as with a materialised K', and the
+    # output must equal, bit for bit, the same kernel reading a materialised K' (PBS_FLAG_RUNNING_MAX_ONLY).
+    w, res = _oracle_run(oracle, name, sigma)
+    p = make_problem(w, flags=w.flags | pbs.FLAG_INDEX_REMAP)
+    pk = make_problem(w, flags=w.flags | pbs.FLAG_INDEX_REMAP | pbs.FLAG_KBAR_IN_WS)
+    K, V = to_dev(w.K, w.dtype), to_dev(w.V, w.dtype)
+    ws = pbs.alloc_workspace(p, pbs.STAGE_BLOCK_MASK)
+    ws.fill_(0xFF)
+    kidx, Kp, Vt = pbs.segment_permute(p, torch.from_numpy(res["s_handoff"]).cuda(), K, V, ws=ws)
+    assert Kp is None
+    np.testing.assert_array_equal(kidx.cpu().numpy(), res["kidx"])
+    np.testing.assert_array_equal(to_host(Vt), vt_layout(res["Vp"], w.block).astype(np.float64))
+    Qp = to_dev(res["Qp"], w.dtype)
+    bits, cnt, cols = pbs.block_mask(pk, Qp, K, ws=ws)           # K is not read: the means are in ws
+    np.testing.assert_array_equal(mask_from_bits(bits, w.T), res["mask"])
+    np.testing.assert_array_equal(cnt.cpu().numpy(), res["row_cnt"])
+    qd = i32_dev(res["qidx"]) if sigma else None
+    Op, lse = pbs.attn_fwd(p, Qp, K, Vt, qd, kidx, cnt, cols, want_lse=True)
+    torch.cuda.synchronize()
+    check_close(to_host(Op), res["Op"], w.dtype, name + " O' with index remapping")
+    np.testing.assert_allclose(lse.cpu().numpy(), res["lse"], rtol=0, atol=2e-2)
+    p_mat = make_problem(w, flags=w.flags | pbs.FLAG_RUNNING_MAX_ONLY)
+    Om, lsem = pbs.attn_fwd(p_mat, Qp, to_dev(res["Kp"], w.dtype), Vt, qd, kidx, cnt, cols, want_lse=True)
+    assert torch.equal(Op, Om) and torch.equal(lse, lsem)
+    # shapes the remapping kernels do not serve are refused
+    if name == "bf16_b128":
+        import ctypes
+        bad = pbs.problem(1, 2, 2, 256, 64, 64, 128, "bf16", flags=pbs.FLAG_INDEX_REMAP)
+        x = torch.zeros(64, device="cuda")
+        assert pbs.load_library().pbs_attn_fwd(ctypes.byref(bad), *([x.data_ptr()] * 3), None, *([x.data_ptr()] * 4),
+                                                None, None, 0, None) == 3
+
+
 @pytest.mark.parametrize("on_permuted_keys", [False, True])
 @pytest.mark.parametrize("name", CASES + ["bf16_even"])
 def test_key_aware_query_permutation(lib, oracle, oracle_variants, name, on_permuted_keys):
