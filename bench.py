@@ -151,6 +151,18 @@ def main():
                          "query block's own segment from that copy: the blocks up to the diagonal, only the diagonal "
                          "one under the causal test (the same visible keys as the R permuted blocks of the segment, so "
                          "the same output)")
+    ap.add_argument("--proxy", choices=["last", "random", "avg"], default="last",
+                    help="which queries stand for all queries in the importance score: the last block (Eq. 4, the "
+                         "paper's method), 128 positions drawn at random from a seed (Random-Query-Attn), or the average "
+                         "query (Avg-Query-Attn); the other two are the paper's ablations, named so in config.workload")
+    ap.add_argument("--key-aware-sigma", action="store_true",
+                    help="also permute the queries, with the key-aware query permutation the paper ablates (sigma from "
+                         "pbs_query_permutation on K', Q' gathered, output scattered back); adds the stage "
+                         "'query_permute' and makes pbs_unpermute do real work; the own-segment shortcut is off then")
+    ap.add_argument("--index-remap", action="store_true",
+                    help="PBS_FLAG_INDEX_REMAP: no K' is materialised, the attention kernel gathers its K tiles from K "
+                         "through kidx (the index remapping of the appendix 'Memory Overhead'); runs on the "
+                         "running-maximum kernel")
     ap.add_argument("--dense-baseline", action="store_true",
                     help="after the timed region, also time plain causal attention in token order through the same "
                          "kernel (three more attention passes) and report the sparse layer's speed-up over it")
@@ -176,45 +188,73 @@ def main():
         w.extra = {k: v for k, v in w.extra.items() if k != "planted"}      # keyed by kv head
         w.h_kv, w.name = w.h_q, w.name + "_replicated_kv"
     given = "row_cnt" in w.extra                      # config 5: caller-supplied block lists, identity key order
-    token_copy = not (args.no_token_order_copy or given)
-    flags = w.flags | (pbs.FLAG_TOKEN_ORDER_COPY if token_copy else 0)
+    variant = (args.proxy != "last") or args.key_aware_sigma or args.index_remap
+    if args.key_aware_sigma and args.index_remap:
+        raise SystemExit("--key-aware-sigma takes its centroids from K', which --index-remap does not materialise")
+    if variant and given:
+        raise SystemExit("--proxy / --key-aware-sigma / --index-remap need a workload that runs the whole path")
+    token_copy = not (args.no_token_order_copy or given or args.key_aware_sigma or args.index_remap)
+    flags = w.flags | (pbs.FLAG_TOKEN_ORDER_COPY if token_copy else 0) | (pbs.FLAG_INDEX_REMAP if args.index_remap else 0)
+    if variant:
+        w.name += "".join(["_proxy_" + args.proxy if args.proxy != "last" else "",
+                           "_key_aware_sigma" if args.key_aware_sigma else "", "_index_remap" if args.index_remap else ""])
     p = pbs.problem(w.batch, w.h_q, w.h_kv, w.n, w.d, w.block, w.segment, w.dtype, tau=w.tau, flags=flags)
     Q, K, V = to_dev(w.Q, w.dtype), to_dev(w.K, w.dtype), to_dev(w.V, w.dtype)
-    pipe = pbs.Pipeline(p)
+    pipe = pbs.Pipeline(p, use_sigma=args.key_aware_sigma)
+    if args.key_aware_sigma:
+        qidx_buf = torch.empty((w.batch, w.h_q, w.n), dtype=torch.int32, device="cuda")
+        ws6 = pbs.alloc_workspace(p, pbs.STAGE_QUERY_PERMUTE)
+    qrows = None
+    if args.proxy == "random":
+        from paper_2510_21270_amd import workloads as wl_
+        qrows = torch.from_numpy(wl_.random_query_rows(w.extra.get("seed", 0), w.n, 128)).cuda()
+    proxy_code = {"last": pbs.PROXY_LAST_BLOCK, "random": pbs.PROXY_QUERY_ROWS, "avg": pbs.PROXY_AVG_QUERY}[args.proxy]
     if given:
         row_cnt = torch.from_numpy(w.extra["row_cnt"]).cuda()
         col_idx = torch.from_numpy(w.extra["col_idx"]).cuda()
 
-    names = ["key_scores", "segment_permute", "block_mask", "attn_fwd", "unpermute"]
+    names = ["key_scores", "segment_permute", "query_permute", "block_mask", "attn_fwd", "unpermute"]
 
     def step(events=None):
         def mark(k):
             if events is not None:
                 events[k].record()
         mark(0)
+        qidx = None
         if given:
             mark(1)
             pbs.segment_permute(p, None, K, V, pipe.kidx, pipe.Kp, pipe.Vt)
             mark(2)
             mark(3)
+            mark(4)
             pbs.attn_fwd(p, Q, pipe.Kp, pipe.Vt, None, pipe.kidx, row_cnt, col_idx, pipe.Op, ws=pipe.ws4)
         else:
-            pbs.key_scores(p, Q, K, pipe.scores, pipe.ws1)
+            if args.proxy == "last":
+                pbs.key_scores(p, Q, K, pipe.scores, pipe.ws1)
+            else:
+                pbs.key_scores_proxy(p, proxy_code, qrows, Q, K, pipe.scores, pipe.ws1)
             mark(1)
-            pbs.segment_permute(p, None if args.no_permute else pipe.scores, K, V, pipe.kidx, pipe.Kp, pipe.Vt,
+            pbs.segment_permute(p, None if args.no_permute else pipe.scores, K, V, pipe.kidx,
+                                None if args.index_remap else pipe.Kp, pipe.Vt,
                                 ws=pipe.ws3)          # the block means of K' come out of the gather
+            keys = K if args.index_remap else pipe.Kp  # with index remapping the attention reads the caller's K
             mark(2)
-            pbs.block_mask(pipe.p_kbar, Q, pipe.Kp, pipe.mask_bits, pipe.row_cnt, pipe.col_idx, pipe.ws3)
+            Qp = Q
+            if args.key_aware_sigma:
+                qidx = pbs.query_permutation(p, Q, pipe.Kp, qidx_buf, ws6)
+                Qp = pbs.permute_rows(p, Q, qidx, pipe.Qp)
             mark(3)
-            pbs.attn_fwd(p, Q, pipe.Kp, pipe.Vt, None, pipe.kidx, pipe.row_cnt, pipe.col_idx, pipe.Op, ws=pipe.ws4)
-        mark(4)
-        pbs.unpermute(p, pipe.Op, None, pipe.O)        # P_sigma = I in the paper's main setting: nothing to move
+            pbs.block_mask(pipe.p_kbar, Qp, keys, pipe.mask_bits, pipe.row_cnt, pipe.col_idx, pipe.ws3)
+            mark(4)
+            pbs.attn_fwd(p, Qp, keys, pipe.Vt, qidx, pipe.kidx, pipe.row_cnt, pipe.col_idx, pipe.Op, ws=pipe.ws4)
         mark(5)
+        pbs.unpermute(p, pipe.Op, qidx, pipe.O)        # P_sigma = I in the paper's main setting: nothing to move
+        mark(6)
 
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(args.steps)]
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(7)] for _ in range(args.steps)]
     t0 = time.perf_counter()
     for k in range(args.steps):
         step(evs[k])
@@ -268,7 +308,7 @@ def main():
         extras["plain_copy"] = {"ms": ms_copy, "GBps": nbytes / ms_copy / 1e6, "bytes": nbytes}
         extras["unpermute_random_sigma"] = {"ms": ms_sigma, "GBps": (nbytes + sigma.numel() * 4) / ms_sigma / 1e6}
         del scratch, sigma
-        if args.coverage and not given:
+        if args.coverage and not given and not variant:
             # true attention mass inside the selected blocks (two more attention passes, untimed)
             _, lse_sel = pbs.attn_fwd(p, Q, pipe.Kp, pipe.Vt, None, pipe.kidx, pipe.row_cnt, pipe.col_idx, pipe.Op,
                                       want_lse=True, ws=pipe.ws4)
@@ -280,7 +320,7 @@ def main():
             extras["attention_mass_covered"] = {"mean": float(cov.mean()), "min_row": float(cov.min()),
                                                 "rows_below_tau": float((cov < w.tau).float().mean())}
             del cov
-        if args.dense_baseline and not given:
+        if args.dense_baseline and not given and not variant:
             # full causal attention in token order through the same kernel (every block up to the diagonal listed):
             # the dense pass that the paper's speed-ups are quoted against, on this GPU; overwrites K', V' and O'
             pbs.segment_permute(p, None, K, V, pipe.kidx, pipe.Kp, pipe.Vt)
@@ -300,7 +340,7 @@ def main():
         rand_rate, rand_mhz = pbs.mfma_rate_probe(True)
         extras["mfma_alone_tflops"] = {"zero_operands": zero_rate, "random_operands": rand_rate}
         extras["shader_clock_mhz"] = {"mfma_alone_zero_operands": zero_mhz, "mfma_alone_random_operands": rand_mhz}
-        if not given:
+        if not given and not variant:
             # the clock pbs_attn_fwd runs at: one watching wave on a second stream beside two attention launches
             def two_attention_launches():
                 for _ in range(2):
