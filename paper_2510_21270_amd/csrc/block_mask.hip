@@ -162,16 +162,19 @@ __global__ __launch_bounds__(64 * RB) __attribute__((amdgpu_waves_per_eu(1, 4)))
 #pragma unroll
         for (int u = 0; u < VEC; ++u) acc[u] = 0.0;
         if (w < rows) {
+            // sixteen 16-byte loads in flight per lane (a block of 128 rows of 256 bytes is two rounds): the read of Q'
+            // is the one large HBM stream of this kernel and a workgroup does nothing else while it waits for it
+            constexpr int U = 16;
             const E *X = Qp + (size_t)(bhq0 + w) * g.n * g.d + cg * VEC;
-            for (int r0 = lo + rg; r0 < hi; r0 += 4 * RG) {
-                vec_t v[4];
+            for (int r0 = lo + rg; r0 < hi; r0 += U * RG) {
+                vec_t v[U];
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
+                for (int q = 0; q < U; ++q) {
                     v[q] = vec_t{};
                     if (r0 + q * RG < hi) v[q] = *reinterpret_cast<const vec_t *>(X + (size_t)(r0 + q * RG) * g.d);
                 }
 #pragma unroll
-                for (int q = 0; q < 4; ++q)
+                for (int q = 0; q < U; ++q)
                     if (r0 + q * RG < hi)
 #pragma unroll
                         for (int u = 0; u < VEC; ++u) acc[u] += (double)ElemTraits<E>::to_float(v[q][u]);
@@ -197,18 +200,19 @@ __global__ __launch_bounds__(64 * RB) __attribute__((amdgpu_waves_per_eu(1, 4)))
         for (int row = 0; row < RB; ++row)
 #pragma unroll
             for (int c = 0; c < 4; ++c) acc[row][c] = 0.0;
-        double2v cur[4][2], nxt[4][2];
+        // two register buffers of four features each, filled alternately: the loads of one are in flight while the
+        // other is multiplied (scheduling barriers keep the compiler from moving a buffer's loads down to its use)
+        double2v bufa[4][2], bufb[4][2];
         auto fetch = [&](double2v (&kv)[4][2], int e) {
+            const int ec = e < g.d ? e : g.d - 4;              // past the end: re-read the last features (unused)
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                const double2v *src = reinterpret_cast<const double2v *>(kt + (size_t)(e + u) * Ts + j);
+                const double2v *src = reinterpret_cast<const double2v *>(kt + (size_t)(ec + u) * Ts + j);
                 kv[u][0] = src[0];
                 kv[u][1] = src[1];
             }
         };
-        fetch(cur, 0);
-        for (int e = 0; e < g.d; e += 4) {
-            fetch(nxt, e + 4 < g.d ? e + 4 : e);             // the last round re-reads its own features (unused)
+        auto multiply = [&](const double2v (&kv)[4][2], int e) {
 #pragma unroll
             for (int u = 0; u < 4; ++u)
 #pragma unroll
@@ -216,13 +220,19 @@ __global__ __launch_bounds__(64 * RB) __attribute__((amdgpu_waves_per_eu(1, 4)))
                     const double q = qs[e + u][row];
 #pragma unroll
                     for (int c = 0; c < 4; ++c)
-                        acc[row][c] = __builtin_fma(q, cur[u][c >> 1][c & 1], acc[row][c]);
+                        acc[row][c] = __builtin_fma(q, kv[u][c >> 1][c & 1], acc[row][c]);
                 }
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                cur[u][0] = nxt[u][0];
-                cur[u][1] = nxt[u][1];
-            }
+        };
+        fetch(bufa, 0);
+        for (int e = 0; e < g.d; e += 8) {                     // d is 64 or 128
+            fetch(bufb, e + 4);
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(bufa, e);
+            __builtin_amdgcn_sched_barrier(0);
+            fetch(bufa, e + 8);
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(bufb, e + 4);
+            __builtin_amdgcn_sched_barrier(0);
         }
 #pragma unroll
         for (int row = 0; row < RB; ++row)
