@@ -395,7 +395,9 @@ def main():
         hbm_gbs = tile_bytes / (stage_ms["attn_fwd"] * 1e-3) / 1e9
         roofline["frac_mfma"] = roofline["frac"]
         roofline["frac_hbm_unshared_tiles"] = hbm_gbs / HBM_PEAK_GBS
-        if roofline["frac_hbm_unshared_tiles"] > roofline["frac_mfma"]:
+        # (above 1 the model is refuted: tiles are being shared in the caches, as they are at high densities, where
+        # the heads of a cohort list many of the same blocks, and the line stays with the matrix bound)
+        if roofline["frac_mfma"] < roofline["frac_hbm_unshared_tiles"] <= 1.0:
             roofline.update(bound="hbm", achieved=hbm_gbs, peak=HBM_PEAK_GBS, unit="GB/s",
                             frac=hbm_gbs / HBM_PEAK_GBS)
             roofline.pop("frac_from_visited_blocks")
