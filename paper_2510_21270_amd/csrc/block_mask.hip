@@ -114,36 +114,49 @@ __device__ inline MassCount mass_at_least(const double *pr, int ni64, int lane, 
     return {wave_sum_dpp(acc), cnt};
 }
 
-// (the LDS a workgroup needs admits four of them per compute unit at T = 1024: registers for four waves per SIMD)
-template <int RB, typename E>
-__global__ __launch_bounds__(64 * RB) __attribute__((amdgpu_waves_per_eu(1, 4))) void select_kernel(const E *__restrict__ Qp,           // [bhq][n][d]
-                                                         const double *__restrict__ KbarT,   // [bhkv][d][Ts]
-                                                         uint64_t *__restrict__ mask_bits,
-                                                         int32_t *__restrict__ row_cnt,
-                                                         int32_t *__restrict__ col_idx, Geo g, int chunks, int Tpad, int Ts)
-{
-    constexpr int THREADS = 64 * RB;
-    extern __shared__ __align__(16) unsigned char smem_raw[];
-    double *prob = reinterpret_cast<double *>(smem_raw);             // [RB][Tpad]
-    __shared__ __align__(16) double qs[128][RB];                     // block means of the RB query rows, feature-major
+// QB query blocks (i0 = QB * blockIdx.x and the next ones) of RB query heads per workgroup: RT = RB * QB rows, one wave
+// each.  Neighbouring query blocks see the same pooled keys (the later one a few more columns), so with QB = 2 a
+// 16-byte load of pooled keys feeds twice the multiply-adds and the logits need half the round trips to L2.
+// Query blocks are taken from the last one down: the long rows start first, the short ones fill the tail.
+constexpr int kPairedLds = 64 * 1024;
 
-    const int i = blockIdx.x;
+template <int RB, int QB, typename E>
+__global__ __launch_bounds__(64 * RB * QB) __attribute__((amdgpu_waves_per_eu(1, 4)))
+void select_kernel(const E *__restrict__ Qp,           // [bhq][n][d]
+                   const double *__restrict__ KbarT,   // [bhkv][d][Ts]
+                   uint64_t *__restrict__ mask_bits, int32_t *__restrict__ row_cnt, int32_t *__restrict__ col_idx,
+                   Geo g, int chunks, int Tpad, int Ts)
+{
+    constexpr int RT = RB * QB;                                      // rows (= waves) of the workgroup
+    constexpr int THREADS = 64 * RT;
+    constexpr int CT = 4 / QB;                                       // columns per thread: 4 * 64 * RB per pass
+    constexpr int FD = 4 * QB;                                       // features per register buffer
+    static_assert(QB == 1 || QB == 2, "column tile is one or two 16-byte loads");
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    double *prob = reinterpret_cast<double *>(smem_raw);             // [RT][Tpad]
+    __shared__ __align__(16) double qs[128][RT];                     // block means of the RT query rows, feature-major
+
+    const int i0 = (g.T - 1) / QB * QB - QB * (int)blockIdx.x;       // first query block of this workgroup
     const int bhk = blockIdx.y / chunks, chunk = blockIdx.y % chunks;
     const int b = bhk / g.h_kv, hk = bhk % g.h_kv;
     const int rows = min(RB, g.r - chunk * RB);                      // query heads handled here
     const int bhq0 = b * g.h_q + hk * g.r + chunk * RB;
-    const int ni = allowed_cols(i, g);
     const int tid = threadIdx.x;
+    const int w = tid >> 6, lane = tid & 63;
+    const int wq = w / RB, wh = w % RB;                              // this wave's query block (i0 + wq) and head
+    const int i = i0 + wq;
+    const bool active = i < g.T && wh < rows;
+    const int nblk = min(QB, g.T - i0);                              // query blocks present
+    const int ni_all = allowed_cols(i0 + nblk - 1, g);               // the last one sees the most columns
 
-    // Block mean of query block i of row w, by wave w (sums of storage values in fp64; 16-byte column groups, four
-    // loads in flight per lane, then the row groups of the wave are added up).  Pooling Q' here instead of in a
-    // kernel of its own lets the 1 GiB read of Q' overlap with the arithmetic of other workgroups.
+    // Block mean of query block i of head wh, by wave w (sums of storage values in fp64; 16-byte column groups,
+    // sixteen loads in flight per lane, then the row groups of the wave are added up).  Pooling Q' here instead of in
+    // a kernel of its own lets the 1 GiB read of Q' overlap with the arithmetic of other workgroups.
     // fp32 storage: every lane owns columns and adds their rows in ascending order (see the note at the top).
     if constexpr (sizeof(E) == 4) {
-        const int w = tid >> 6, lane = tid & 63;
         const int lo = i * g.block, hi = min(g.n, lo + g.block);
-        if (w < rows) {
-            const E *X = Qp + (size_t)(bhq0 + w) * g.n * g.d;
+        if (active) {
+            const E *X = Qp + (size_t)(bhq0 + wh) * g.n * g.d;
             for (int e = lane; e < g.d; e += 64) {
                 double s = 0.0;
                 for (int row = lo; row < hi; ++row) s += (double)ElemTraits<E>::to_float(X[(size_t)row * g.d + e]);
@@ -153,7 +166,6 @@ __global__ __launch_bounds__(64 * RB) __attribute__((amdgpu_waves_per_eu(1, 4)))
     } else {
         constexpr int VEC = 16 / sizeof(E);
         typedef E vec_t __attribute__((ext_vector_type(VEC)));
-        const int w = tid >> 6, lane = tid & 63;
         const int cpr = g.d / VEC;                                   // 8 .. 32 column groups
         const int RG = 64 / cpr;                                     // row groups of a wave
         const int cg = lane % cpr, rg = lane / cpr;
@@ -161,11 +173,11 @@ __global__ __launch_bounds__(64 * RB) __attribute__((amdgpu_waves_per_eu(1, 4)))
         double acc[VEC];
 #pragma unroll
         for (int u = 0; u < VEC; ++u) acc[u] = 0.0;
-        if (w < rows) {
-            // sixteen 16-byte loads in flight per lane (a block of 128 rows of 256 bytes is two rounds): the read of Q'
-            // is the one large HBM stream of this kernel and a workgroup does nothing else while it waits for it
+        if (active) {
+            // (a block of 128 rows of 256 bytes is two rounds): the read of Q' is the one large HBM stream of this
+            // kernel and a workgroup does nothing else while it waits for it
             constexpr int U = 16;
-            const E *X = Qp + (size_t)(bhq0 + w) * g.n * g.d + cg * VEC;
+            const E *X = Qp + (size_t)(bhq0 + wh) * g.n * g.d + cg * VEC;
             for (int r0 = lo + rg; r0 < hi; r0 += U * RG) {
                 vec_t v[U];
 #pragma unroll
@@ -183,68 +195,74 @@ __global__ __launch_bounds__(64 * RB) __attribute__((amdgpu_waves_per_eu(1, 4)))
         for (int o = cpr; o < 64; o <<= 1)
 #pragma unroll
             for (int u = 0; u < VEC; ++u) acc[u] += __shfl_xor(acc[u], o, 64);
-        if (rg == 0)
+        if (rg == 0 && active)
 #pragma unroll
             for (int u = 0; u < VEC; ++u) qs[cg * VEC + u][w] = acc[u] / (double)(hi - lo);
     }
     __syncthreads();
 
-    // logits: fused multiply-adds in the order e = 0..d-1; columns j .. j + 3 of every row per thread (columns at or
-    // beyond ni are computed from whatever the padded Kbar rows hold and dropped).  The pooled keys of the next four
-    // features are requested before the current four are multiplied.
+    // logits: fused multiply-adds in the order e = 0..d-1; columns j .. j + CT - 1 of every row per thread (columns at
+    // or beyond a row's own count are computed from whatever the padded Kbar rows hold and never read; rows that are
+    // not there from whatever qs holds).  Two register buffers of FD features each, filled alternately: the loads of
+    // one are in flight while the other is multiplied (scheduling barriers keep the compiler from moving a buffer's
+    // loads down to its use).
     const double *kt = KbarT + (size_t)bhk * g.d * Ts;
     typedef double double2v __attribute__((ext_vector_type(2)));
-    for (int j = 4 * tid; j < ni; j += 4 * THREADS) {
-        double acc[RB][4];
+    for (int j = CT * tid; j < ni_all; j += CT * THREADS) {
+        double acc[RT][CT];
 #pragma unroll
-        for (int row = 0; row < RB; ++row)
+        for (int row = 0; row < RT; ++row)
 #pragma unroll
-            for (int c = 0; c < 4; ++c) acc[row][c] = 0.0;
-        // two register buffers of four features each, filled alternately: the loads of one are in flight while the
-        // other is multiplied (scheduling barriers keep the compiler from moving a buffer's loads down to its use)
-        double2v bufa[4][2], bufb[4][2];
-        auto fetch = [&](double2v (&kv)[4][2], int e) {
-            const int ec = e < g.d ? e : g.d - 4;              // past the end: re-read the last features (unused)
+            for (int c = 0; c < CT; ++c) acc[row][c] = 0.0;
+        double kva[FD][CT], kvb[FD][CT];
+        auto fetch = [&](double (&kv)[FD][CT], int e) {
+            const int ec = e < g.d ? e : g.d - FD;             // past the end: re-read the last features (unused)
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const double2v *src = reinterpret_cast<const double2v *>(kt + (size_t)(ec + u) * Ts + j);
-                kv[u][0] = src[0];
-                kv[u][1] = src[1];
+            for (int u = 0; u < FD; ++u) {
+                const double *src = kt + (size_t)(ec + u) * Ts + j;
+                const double2v lo2 = *reinterpret_cast<const double2v *>(src);
+                kv[u][0] = lo2[0];
+                kv[u][1] = lo2[1];
+                if constexpr (CT == 4) {
+                    const double2v hi2 = *reinterpret_cast<const double2v *>(src + 2);
+                    kv[u][2] = hi2[0];
+                    kv[u][3] = hi2[1];
+                }
             }
         };
-        auto multiply = [&](const double2v (&kv)[4][2], int e) {
+        auto multiply = [&](const double (&kv)[FD][CT], int e) {
 #pragma unroll
-            for (int u = 0; u < 4; ++u)
+            for (int u = 0; u < FD; ++u)
 #pragma unroll
-                for (int row = 0; row < RB; ++row) {
+                for (int row = 0; row < RT; ++row) {
                     const double q = qs[e + u][row];
 #pragma unroll
-                    for (int c = 0; c < 4; ++c)
-                        acc[row][c] = __builtin_fma(q, kv[u][c >> 1][c & 1], acc[row][c]);
+                    for (int c = 0; c < CT; ++c) acc[row][c] = __builtin_fma(q, kv[u][c], acc[row][c]);
                 }
         };
-        fetch(bufa, 0);
-        for (int e = 0; e < g.d; e += 8) {                     // d is 64 or 128
-            fetch(bufb, e + 4);
+        fetch(kva, 0);
+        for (int e = 0; e < g.d; e += 2 * FD) {                // d is 64 or 128
+            fetch(kvb, e + FD);
             __builtin_amdgcn_sched_barrier(0);
-            multiply(bufa, e);
+            multiply(kva, e);
             __builtin_amdgcn_sched_barrier(0);
-            fetch(bufa, e + 8);
+            fetch(kva, e + 2 * FD);
             __builtin_amdgcn_sched_barrier(0);
-            multiply(bufb, e + 4);
+            multiply(kvb, e + FD);
             __builtin_amdgcn_sched_barrier(0);
         }
 #pragma unroll
-        for (int row = 0; row < RB; ++row)
+        for (int row = 0; row < RT; ++row)
 #pragma unroll
-            for (int c = 0; c < 4; ++c)
-                if (j + c < ni) prob[row * Tpad + j + c] = __dmul_rn(acc[row][c], (double)g.scale);
+            for (int c = 0; c < CT; ++c)
+                if (j + c < ni_all) prob[row * Tpad + j + c] = __dmul_rn(acc[row][c], (double)g.scale);
     }
     __syncthreads();
 
-    // from here on wave `row` works alone on its row
-    const int row = tid >> 6, lane = tid & 63;
-    if (row >= rows) return;
+    // from here on wave w works alone on its row
+    if (!active) return;
+    const int row = w;
+    const int ni = allowed_cols(i, g);
     double *pr = prob + row * Tpad;
     const int ni64 = (ni + 63) & ~63;
     double lmax = -INFINITY;
@@ -312,7 +330,7 @@ __global__ __launch_bounds__(64 * RB) __attribute__((amdgpu_waves_per_eu(1, 4)))
     const int seg = i / g.R;
     const int flo = seg < g.G ? seg * g.R : i;
     const int W = (g.T + 63) >> 6;
-    const size_t orow = (size_t)(bhq0 + row) * g.T + i;
+    const size_t orow = (size_t)(bhq0 + wh) * g.T + i;
     uint64_t *mrow = mask_bits + orow * W;
     int32_t *crow = col_idx + orow * g.T;
     const uint64_t below = (1ull << lane) - 1ull;
@@ -335,22 +353,33 @@ __global__ __launch_bounds__(64 * RB) __attribute__((amdgpu_waves_per_eu(1, 4)))
     if (lane == 0) row_cnt[orow] = base;
 }
 
-template <int RB, typename E>
-static pbs_status launch_select(const E *Qp, const double *KbarT, uint64_t *mask_bits, int32_t *row_cnt,
-                                int32_t *col_idx, const Geo &g, hipStream_t s)
+template <int RB, int QB, typename E>
+static pbs_status launch_select_qb(const E *Qp, const double *KbarT, uint64_t *mask_bits, int32_t *row_cnt,
+                                   int32_t *col_idx, const Geo &g, hipStream_t s)
 {
     const int chunks = (g.r + RB - 1) / RB;
     const int Tpad = (g.T + 63) & ~63;
     const int Ts = kbar_stride(g.T);
-    const size_t lds = (size_t)RB * Tpad * sizeof(double);
+    const size_t lds = (size_t)RB * QB * Tpad * sizeof(double);
     static std::atomic<unsigned long long> lds_raised{0};
     if (lds > 32 * 1024) {
-        const pbs_status st = raise_lds_limit(reinterpret_cast<const void *>(&select_kernel<RB, E>),
-                                              RB * kMaxT * (int)sizeof(double), lds_raised);
+        const pbs_status st = raise_lds_limit(reinterpret_cast<const void *>(&select_kernel<RB, QB, E>),
+                                              QB == 1 ? RB * kMaxT * (int)sizeof(double) : kPairedLds, lds_raised);
         if (st != PBS_OK) return st;
     }
-    return launch((select_kernel<RB, E>), dim3(g.T, g.batch * g.h_kv * chunks), dim3(64 * RB), lds, s, Qp, KbarT,
-                       mask_bits, row_cnt, col_idx, g, chunks, Tpad, Ts);
+    return launch((select_kernel<RB, QB, E>), dim3((g.T + QB - 1) / QB, g.batch * g.h_kv * chunks), dim3(64 * RB * QB),
+                  lds, s, Qp, KbarT, mask_bits, row_cnt, col_idx, g, chunks, Tpad, Ts);
+}
+
+// two query blocks per workgroup while their logits fit 64 KiB of LDS (two such workgroups per compute unit)
+template <int RB, typename E>
+static pbs_status launch_select(const E *Qp, const double *KbarT, uint64_t *mask_bits, int32_t *row_cnt,
+                                int32_t *col_idx, const Geo &g, hipStream_t s)
+{
+    const int Tpad = (g.T + 63) & ~63;
+    if ((size_t)RB * 2 * Tpad * sizeof(double) <= (size_t)kPairedLds)
+        return launch_select_qb<RB, 2>(Qp, KbarT, mask_bits, row_cnt, col_idx, g, s);
+    return launch_select_qb<RB, 1>(Qp, KbarT, mask_bits, row_cnt, col_idx, g, s);
 }
 
 // Block means of K' into KbarT ([kv head][feature][kbar_stride(T)] fp64); also called by pbs_segment_permute for the
