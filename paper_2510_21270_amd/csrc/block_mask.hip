@@ -183,7 +183,7 @@ void select_kernel(const E *__restrict__ Qp,           // [bhq][n][d]
 #pragma unroll
                 for (int q = 0; q < U; ++q) {
                     v[q] = vec_t{};
-                    if (r0 + q * RG < hi) v[q] = *reinterpret_cast<const vec_t *>(X + (size_t)(r0 + q * RG) * g.d);
+                    if (r0 + q * RG < hi) v[q] = __builtin_nontemporal_load(reinterpret_cast<const vec_t *>(X + (size_t)(r0 + q * RG) * g.d));
                 }
 #pragma unroll
                 for (int q = 0; q < U; ++q)

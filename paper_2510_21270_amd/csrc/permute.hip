@@ -85,6 +85,15 @@ __global__ __launch_bounds__(256) void iota_kernel(int32_t *__restrict__ idx, in
     }
 }
 
+// A 16-byte load of a source row.  Rows that are read once are read past the caches' retention (non-temporal); with
+// the token-order copy every row is read twice, by neighbouring workgroups, and the second read should find it.
+template <bool TWICE, typename T>
+__device__ inline T load_once_or_twice(const T *ptr)
+{
+    if constexpr (TWICE) return *ptr;
+    else return __builtin_nontemporal_load(ptr);
+}
+
 // ---------------------------------------------------------------------------------------------
 // Row gather / scatter in 16-byte chunks; cpr = chunks per row (a power of two).
 // SCATTER = false: dst[row] = src[head(row), idx[row]]     (X' = P X)
@@ -94,7 +103,7 @@ __global__ __launch_bounds__(256) void iota_kernel(int32_t *__restrict__ idx, in
 // copy_stride > 0 (gather only): the grid is twice as wide; odd workgroups write a plain copy of the same range of
 // rows copy_stride chunks behind dst (the token-order copy), right next in time to the even workgroup that gathers
 // rows of the same segments, so that most of what they read is still in the last-level caches.
-template <bool SCATTER>
+template <bool SCATTER, bool TWICE = false>
 __global__ __launch_bounds__(256) void move_rows_kernel(const uintx4 *__restrict__ src,
                                                         const int32_t *__restrict__ idx,
                                                         uintx4 *__restrict__ dst, int n, int cpr_log2,
@@ -128,13 +137,15 @@ __global__ __launch_bounds__(256) void move_rows_kernel(const uintx4 *__restrict
             const uint32_t c = c0 + u * 256;
             const bool ok = other[u] >= 0 && other[u] < n;
             v[u] = uintx4{0u, 0u, 0u, 0u};
-            if (SCATTER ? c < end : ok) v[u] = hsrc[SCATTER ? c : ((uint32_t)other[u] << cpr_log2) + (c & cmask)];
+            if (SCATTER ? c < end : ok)
+                v[u] = load_once_or_twice<TWICE>(hsrc + (SCATTER ? c : ((uint32_t)other[u] << cpr_log2) + (c & cmask)));
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const uint32_t c = c0 + u * 256;
             const bool ok = other[u] >= 0 && other[u] < n;
-            if (SCATTER ? ok : c < end) hdst[SCATTER ? ((uint32_t)other[u] << cpr_log2) + (c & cmask) : c] = v[u];
+            if (SCATTER ? ok : c < end)
+                __builtin_nontemporal_store(v[u], hdst + (SCATTER ? ((uint32_t)other[u] << cpr_log2) + (c & cmask) : c));
         }
     }
 }
@@ -148,6 +159,7 @@ __global__ __launch_bounds__(256) void move_rows_kernel(const uintx4 *__restrict
 // every block the 256 / cpr row slots of a column meet in LDS.  dst == NULL: only the block means are produced (index
 // remapping: the attention kernel gathers the rows itself and no K' is written).
 // ---------------------------------------------------------------------------------------------
+template <bool TWICE>
 __global__ __launch_bounds__(256) void gather_pool_kernel(const uintx4 *__restrict__ src,
                                                           const int32_t *__restrict__ idx, uintx4 *__restrict__ dst,
                                                           int n, int cpr_log2, size_t copy_stride,
@@ -183,13 +195,14 @@ __global__ __launch_bounds__(256) void gather_pool_kernel(const uintx4 *__restri
         for (int u = 0; u < U; ++u) {
             const uint32_t c = base + threadIdx.x + u * 256;
             v[u] = uintx4{0u, 0u, 0u, 0u};
-            if (other[u] >= 0 && other[u] < n) v[u] = hsrc[((uint32_t)other[u] << cpr_log2) + (c & cmask)];
+            if (other[u] >= 0 && other[u] < n)
+                v[u] = load_once_or_twice<TWICE>(hsrc + ((uint32_t)other[u] << cpr_log2) + (c & cmask));
         }
         if (dst) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const uint32_t c = base + threadIdx.x + u * 256;
-                if (c < end) hdst[c] = v[u];
+                if (c < end) __builtin_nontemporal_store(v[u], hdst + c);
             }
         }
         if (plain) continue;                                  // uniform: the token-order copy is not pooled
@@ -232,7 +245,7 @@ __global__ __launch_bounds__(256) void gather_pool_kernel(const uintx4 *__restri
 // ---------------------------------------------------------------------------------------------
 // copy_stride > 0: the grid is twice as wide; odd workgroups transpose the same key block without the permutation
 // into the copy copy_stride elements behind Vt (see move_rows_kernel).
-template <typename E>
+template <typename E, bool TWICE>
 __global__ __launch_bounds__(256) void gather_vt_kernel(const E *__restrict__ V, const int32_t *__restrict__ kidx,
                                                         E *__restrict__ Vt, int n, int d, int block, int T,
                                                         size_t copy_stride)
@@ -267,7 +280,7 @@ __global__ __launch_bounds__(256) void gather_vt_kernel(const E *__restrict__ V,
             const int c = c0 + u * 256;
             v[u] = vec_t{};
             if (from[u] >= 0 && from[u] < n)
-                v[u] = *reinterpret_cast<const vec_t *>(V + (bh * n + from[u]) * (size_t)d + (c % cpr) * VEC);
+                v[u] = load_once_or_twice<TWICE>(reinterpret_cast<const vec_t *>(V + (bh * n + from[u]) * (size_t)d + (c % cpr) * VEC));
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -289,7 +302,7 @@ __global__ __launch_bounds__(256) void gather_vt_kernel(const E *__restrict__ V,
             uintx4 v;
 #pragma unroll
             for (int u = 0; u < 4; ++u) v[u] = x[u];
-            *reinterpret_cast<uintx4 *>(og + (size_t)w * G) = v;
+            __builtin_nontemporal_store(v, reinterpret_cast<uintx4 *>(og + (size_t)w * G));
         } else {                                           // word w holds elements 2w (low half) and 2w + 1
             uintx4 lo, hi;
 #pragma unroll
@@ -297,8 +310,8 @@ __global__ __launch_bounds__(256) void gather_vt_kernel(const E *__restrict__ V,
                 lo[u] = __builtin_amdgcn_perm(x[(2 * u + 1) % VEC], x[(2 * u) % VEC], 0x05040100u);
                 hi[u] = __builtin_amdgcn_perm(x[(2 * u + 1) % VEC], x[(2 * u) % VEC], 0x07060302u);
             }
-            *reinterpret_cast<uintx4 *>(og + (size_t)(2 * w) * G) = lo;
-            *reinterpret_cast<uintx4 *>(og + (size_t)(2 * w + 1) * G) = hi;
+            __builtin_nontemporal_store(lo, reinterpret_cast<uintx4 *>(og + (size_t)(2 * w) * G));
+            __builtin_nontemporal_store(hi, reinterpret_cast<uintx4 *>(og + (size_t)(2 * w + 1) * G));
         }
     }
 }
@@ -314,13 +327,14 @@ static int grid_for(size_t items, int per_block)
     return (int)b;
 }
 
-// grid for move_rows_kernel: enough workgroups to fill the chip, each thread moving a few chunks
-static dim3 move_grid(int n, int cpr, int nbh)
+// grid for move_rows_kernel and gather_pool_kernel: one batch of 4 x 256 chunks (16 KiB) per workgroup -- or `unit`
+// chunks where a workgroup has to own whole key blocks --, so that the workgroups in flight at any time sweep one
+// narrow window of addresses (measured on a plain 1 GiB copy: 5.3 TB/s read + write with 1024 long ranges, 6.3 with
+// 65536 short ones and non-temporal accesses)
+static dim3 move_grid(int n, int cpr, int nbh, size_t unit = 256 * 4)
 {
     const size_t chunks = (size_t)n * cpr;
-    size_t bx = (chunks + 256 * 4 - 1) / (256 * 4);
-    const size_t cap = (size_t)(256 * 32 + nbh - 1) / nbh;
-    if (bx > cap) bx = cap;
+    size_t bx = (chunks + unit - 1) / unit;
     if (bx < 1) bx = 1;
     return dim3((unsigned)bx, (unsigned)nbh);
 }
@@ -382,32 +396,42 @@ extern "C" pbs_status pbs_segment_permute(const pbs_problem *p, const float *sco
     const size_t es = elem_size(p->dtype);
     const int cpr = (int)(g.d * es / 16);
     const size_t vt_half = (size_t)nbh * g.T * g.d * g.block;           // elements
-    dim3 mg = move_grid(g.n, cpr, nbh);
-    if (token_copy) mg.x *= 2;
+
     // with a workspace, the block means of K' are left there for pbs_block_mask: by the gather itself where a key
     // block is a whole number of its 1024-chunk batches (2-byte storage), by the pooling kernel otherwise
     double *kbarT = reinterpret_cast<double *>(ws);
     const bool pool_on_the_way = kbarT && p->dtype == PBS_BF16 && (g.block * cpr) % 1024 == 0;
+    dim3 mg = pool_on_the_way ? move_grid(g.n, cpr, nbh, (size_t)g.block * cpr) : move_grid(g.n, cpr, nbh);
+    if (token_copy) mg.x *= 2;
     if (remap && kbarT && !pool_on_the_way) return PBS_ERR_UNSUPPORTED;   // means without K' only from the gather kernel
+    const size_t kcopy = token_copy ? tok_rows * cpr : (size_t)0;
+    const int Tsk = kbar_stride(g.T), cl = ilog2(cpr);
     if (pool_on_the_way)
-        st = launch(gather_pool_kernel, mg, dim3(256), 0, s, (const uintx4 *)K, (const int32_t *)kidx, (uintx4 *)kdst,
-                    g.n, ilog2(cpr), token_copy ? tok_rows * cpr : (size_t)0, kbarT, g.block, kbar_stride(g.T));
+        st = token_copy ? launch(gather_pool_kernel<true>, mg, dim3(256), 0, s, (const uintx4 *)K, (const int32_t *)kidx,
+                                 (uintx4 *)kdst, g.n, cl, kcopy, kbarT, g.block, Tsk)
+                        : launch(gather_pool_kernel<false>, mg, dim3(256), 0, s, (const uintx4 *)K, (const int32_t *)kidx,
+                                 (uintx4 *)kdst, g.n, cl, kcopy, kbarT, g.block, Tsk);
     else if (kdst)
-        st = launch(move_rows_kernel<false>, mg, dim3(256), 0, s, (const uintx4 *)K, (const int32_t *)kidx,
-                    (uintx4 *)kdst, g.n, ilog2(cpr), token_copy ? tok_rows * cpr : (size_t)0);
+        st = token_copy ? launch((move_rows_kernel<false, true>), mg, dim3(256), 0, s, (const uintx4 *)K,
+                                 (const int32_t *)kidx, (uintx4 *)kdst, g.n, cl, kcopy)
+                        : launch((move_rows_kernel<false, false>), mg, dim3(256), 0, s, (const uintx4 *)K,
+                                 (const int32_t *)kidx, (uintx4 *)kdst, g.n, cl, kcopy);
     if (st != PBS_OK) return st;
     if (kbarT && !pool_on_the_way && (st = launch_pool_keys(p, g, Kp, kbarT, s)) != PBS_OK) return st;
     const dim3 vg(token_copy ? 2 * g.T : g.T, nbh);
+    const size_t vcopy = token_copy ? vt_half : (size_t)0;
     if (p->dtype == PBS_BF16) {
         const size_t lds = (size_t)g.block * g.d * 2 + (size_t)(g.block / 8) * (64 / (vt_group(g.block) / 8)) * 4;   // tile + skew
-        st = launch(gather_vt_kernel<uint16_t>, vg, dim3(256), lds, s, (const uint16_t *)V,
-                           (const int32_t *)kidx, (uint16_t *)Vt, g.n, g.d, g.block, g.T,
-                           token_copy ? vt_half : (size_t)0);
+        st = token_copy ? launch((gather_vt_kernel<uint16_t, true>), vg, dim3(256), lds, s, (const uint16_t *)V,
+                                 (const int32_t *)kidx, (uint16_t *)Vt, g.n, g.d, g.block, g.T, vcopy)
+                        : launch((gather_vt_kernel<uint16_t, false>), vg, dim3(256), lds, s, (const uint16_t *)V,
+                                 (const int32_t *)kidx, (uint16_t *)Vt, g.n, g.d, g.block, g.T, vcopy);
     } else {
         const size_t lds = (size_t)g.block * g.d * 4 + (size_t)(g.block / 4) * (64 / (vt_group(g.block) / 4)) * 4;
-        st = launch(gather_vt_kernel<uint32_t>, vg, dim3(256), lds, s, (const uint32_t *)V,
-                           (const int32_t *)kidx, (uint32_t *)Vt, g.n, g.d, g.block, g.T,
-                           token_copy ? vt_half : (size_t)0);
+        st = token_copy ? launch((gather_vt_kernel<uint32_t, true>), vg, dim3(256), lds, s, (const uint32_t *)V,
+                                 (const int32_t *)kidx, (uint32_t *)Vt, g.n, g.d, g.block, g.T, vcopy)
+                        : launch((gather_vt_kernel<uint32_t, false>), vg, dim3(256), lds, s, (const uint32_t *)V,
+                                 (const int32_t *)kidx, (uint32_t *)Vt, g.n, g.d, g.block, g.T, vcopy);
     }
     return st;
 }
