@@ -117,15 +117,13 @@ static int assign_cmp(const void *pa, const void *pb)
     return a->pos < b->pos ? -1 : (a->pos > b->pos ? 1 : 0);
 }
 
-int pbsv_query_permutation(int batch, int h_q, int h_kv, int n, int d, int block, int segment,
-                           const float *Q, const float *K, int32_t *qidx, int32_t *assigned)
+/* centroids and their reciprocal norms for every (batch, kv head): Kbar [bh][T][d], rinv [bh][T] */
+static int centroids(int nbk, int n, int d, int block, int T, const float *K, double **Kbar_out, double **rinv_out)
 {
-    if (h_kv <= 0 || h_q % h_kv != 0 || n <= 0 || d <= 0 || block <= 0 || segment % block != 0) return 1;
-    const int T = (n + block - 1) / block, R = segment / block, G = n / segment, r = h_q / h_kv;
-    double *Kbar = (double *)malloc(sizeof(double) * (size_t)batch * h_kv * T * d);
-    double *rinv = (double *)malloc(sizeof(double) * (size_t)batch * h_kv * T);
+    double *Kbar = (double *)malloc(sizeof(double) * (size_t)nbk * T * d);
+    double *rinv = (double *)malloc(sizeof(double) * (size_t)nbk * T);
     if (!Kbar || !rinv) { free(Kbar); free(rinv); return 2; }
-    for (int bh = 0; bh < batch * h_kv; ++bh)
+    for (int bh = 0; bh < nbk; ++bh)
         for (int j = 0; j < T; ++j) {
             const int lo = j * block, hi = lo + block < n ? lo + block : n;
             double nsq = 0.0;
@@ -138,6 +136,44 @@ int pbsv_query_permutation(int batch, int h_q, int h_kv, int n, int d, int block
             }
             rinv[(size_t)bh * T + j] = nsq > 0.0 ? 1.0 / sqrt(nsq) : 0.0;
         }
+    *Kbar_out = Kbar;
+    *rinv_out = rinv;
+    return 0;
+}
+
+/* segment g of one query head: out[0 .. segment) = the segment's positions ordered by (assigned centroid, position);
+ * assigned (nullable) is indexed by absolute position.  a: scratch of `segment` entries. */
+static void order_segment(int g, int n, int d, int segment, int R, int T, const float *Qh, const double *kb,
+                          const double *ri, pbsv_assign *a, int32_t *out, int32_t *assigned)
+{
+    const int ncand = (g + 1) * R < T ? (g + 1) * R : T;
+    (void)n;
+    for (int t = 0; t < segment; ++t) {
+        const int pos = g * segment + t;
+        const float *q = Qh + (size_t)pos * d;
+        int best = 0;
+        double ubest = 0.0;
+        for (int j = 0; j < ncand; ++j) {
+            double dot = 0.0;
+            for (int e = 0; e < d; ++e) dot += (double)q[e] * kb[(size_t)j * d + e];
+            const double u = dot * ri[j];
+            if (j == 0 || u > ubest) { ubest = u; best = j; }
+        }
+        a[t].c = best;
+        a[t].pos = pos;
+        if (assigned) assigned[pos] = best;
+    }
+    qsort(a, (size_t)segment, sizeof(pbsv_assign), assign_cmp);
+    for (int t = 0; t < segment; ++t) out[t] = a[t].pos;
+}
+
+int pbsv_query_permutation(int batch, int h_q, int h_kv, int n, int d, int block, int segment,
+                           const float *Q, const float *K, int32_t *qidx, int32_t *assigned)
+{
+    if (h_kv <= 0 || h_q % h_kv != 0 || n <= 0 || d <= 0 || block <= 0 || segment % block != 0) return 1;
+    const int T = (n + block - 1) / block, R = segment / block, G = n / segment, r = h_q / h_kv;
+    double *Kbar, *rinv;
+    if (centroids(batch * h_kv, n, d, block, T, K, &Kbar, &rinv)) return 2;
     int fail = 0;
 #pragma omp parallel for schedule(dynamic)
     for (int bhq = 0; bhq < batch * h_q; ++bhq) {
@@ -145,32 +181,39 @@ int pbsv_query_permutation(int batch, int h_q, int h_kv, int n, int d, int block
         const double *kb = Kbar + ((size_t)(b * h_kv + hk) * T) * d;
         const double *ri = rinv + (size_t)(b * h_kv + hk) * T;
         int32_t *out = qidx + (size_t)bhq * n;
+        int32_t *as = assigned ? assigned + (size_t)bhq * n : NULL;
         pbsv_assign *a = (pbsv_assign *)malloc(sizeof(pbsv_assign) * (size_t)segment);
         if (!a) { fail = 1; continue; }
-        for (int g = 0; g < G; ++g) {
-            const int ncand = (g + 1) * R < T ? (g + 1) * R : T;
-            for (int t = 0; t < segment; ++t) {
-                const int pos = g * segment + t;
-                const float *q = Q + ((size_t)bhq * n + pos) * d;
-                int best = 0;
-                double ubest = 0.0;
-                for (int j = 0; j < ncand; ++j) {
-                    double dot = 0.0;
-                    for (int e = 0; e < d; ++e) dot += (double)q[e] * kb[(size_t)j * d + e];
-                    const double u = dot * ri[j];
-                    if (j == 0 || u > ubest) { ubest = u; best = j; }
-                }
-                a[t].c = best;
-                a[t].pos = pos;
-                if (assigned) assigned[(size_t)bhq * n + pos] = best;
-            }
-            qsort(a, (size_t)segment, sizeof(pbsv_assign), assign_cmp);
-            for (int t = 0; t < segment; ++t) out[g * segment + t] = a[t].pos;
-        }
+        for (int g = 0; g < G; ++g)
+            order_segment(g, n, d, segment, R, T, Q + (size_t)bhq * n * d, kb, ri, a, out + (size_t)g * segment, as);
         for (int pos = G * segment; pos < n; ++pos) {
             out[pos] = pos;
-            if (assigned) assigned[(size_t)bhq * n + pos] = -1;
+            if (as) as[pos] = -1;
         }
+        free(a);
+    }
+    free(Kbar); free(rinv);
+    return fail ? 2 : 0;
+}
+
+/* The same for ONE full segment g of every query head (what a test at full length can afford): qseg [batch, h_q,
+ * segment] = the slice [g*segment, (g+1)*segment) of the qidx that pbsv_query_permutation would write. */
+int pbsv_query_permutation_segment(int batch, int h_q, int h_kv, int n, int d, int block, int segment, int g,
+                                   const float *Q, const float *K, int32_t *qseg)
+{
+    if (h_kv <= 0 || h_q % h_kv != 0 || n <= 0 || d <= 0 || block <= 0 || segment % block != 0) return 1;
+    const int T = (n + block - 1) / block, R = segment / block, G = n / segment, r = h_q / h_kv;
+    if (g < 0 || g >= G) return 1;
+    double *Kbar, *rinv;
+    if (centroids(batch * h_kv, n, d, block, T, K, &Kbar, &rinv)) return 2;
+    int fail = 0;
+#pragma omp parallel for schedule(dynamic)
+    for (int bhq = 0; bhq < batch * h_q; ++bhq) {
+        const int b = bhq / h_q, hq = bhq % h_q, hk = hq / r;
+        pbsv_assign *a = (pbsv_assign *)malloc(sizeof(pbsv_assign) * (size_t)segment);
+        if (!a) { fail = 1; continue; }
+        order_segment(g, n, d, segment, R, T, Q + (size_t)bhq * n * d, Kbar + ((size_t)(b * h_kv + hk) * T) * d,
+                      rinv + (size_t)(b * h_kv + hk) * T, a, qseg + (size_t)bhq * segment, NULL);
         free(a);
     }
     free(Kbar); free(rinv);

@@ -77,3 +77,17 @@ def query_permutation(Q, K, block, segment, want_assigned=False):
     if rc:
         raise RuntimeError("pbsv_query_permutation failed: %d" % rc)
     return (qidx, assigned) if want_assigned else qidx
+
+
+def query_permutation_segment(Q, K, block, segment, g):
+    """The slice [g*segment, (g+1)*segment) of query_permutation's qidx, for one full segment g of every head, at the
+    cost of that segment alone: [B,Hq,segment] int32."""
+    B, Hq, N, d = Q.shape
+    Hkv = K.shape[1]
+    Q, qp = _f32(Q)
+    K, kp = _f32(K)
+    qseg = np.empty((B, Hq, int(segment)), dtype=np.int32)
+    rc = _load().pbsv_query_permutation_segment(B, Hq, Hkv, N, d, int(block), int(segment), int(g), qp, kp, _i32p(qseg))
+    if rc:
+        raise RuntimeError("pbsv_query_permutation_segment failed: %d" % rc)
+    return qseg

@@ -111,6 +111,58 @@ def test_full_size_attention_on_sampled_rows(oracle, name):
     check_close(to_host(Op2[0, 0]), to_host(Op[0, 0]), "bf16", "%s head 0, copy against permuted order" % name)
 
 
+def test_full_size_variants_proxies_query_permutation_and_index_remapping(oracle, oracle_variants):
+    # the variants the paper ablates, at the headline layer's full size (N = 131072, 32 query heads, 8 kv heads), each
+    # against what the oracle can afford there: the two other proxies in full (by value), the key-aware query
+    # permutation on whole segments picked over the sequence (bit-exact), index-remapped attention on sampled rows
+    st = _setup("c3", oracle)
+    w, p, pipe = st["w"], st["p"], st["pipe"]
+    T, R, G = w.T, w.segment // w.block, w.n // w.segment
+    # proxies: 128 positions drawn from a seed; the average query
+    rows = wl.random_query_rows(3, w.n, 128)
+    got = pbs.key_scores_proxy(p, pbs.PROXY_QUERY_ROWS, torch.from_numpy(rows).cuda(), st["Q"], st["K"], pipe.scores,
+                               pipe.ws1)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(got.cpu().numpy().astype(np.float64), oracle_variants.key_scores_proxy(w.Q, w.K, rows),
+                               rtol=2e-3, atol=1e-37)
+    got = pbs.key_scores_proxy(p, pbs.PROXY_AVG_QUERY, None, st["Q"], st["K"], pipe.scores, pipe.ws1)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(got.cpu().numpy().astype(np.float64), oracle_variants.key_scores_proxy(w.Q, w.K),
+                               rtol=2e-3, atol=1e-37)
+    # key-aware sigma on the permuted keys: first, second, a middle and the last segment of every head
+    Kp_d = to_dev(st["Kp"], "bf16")
+    qidx = pbs.query_permutation(p, st["Q"], Kp_d)
+    torch.cuda.synchronize()
+    qh = qidx.cpu().numpy()
+    for g in (0, 1, G // 2, G - 1):
+        want = oracle_variants.query_permutation_segment(w.Q, st["Kp"], w.block, w.segment, g)
+        assert np.array_equal(qh[:, :, g * w.segment:(g + 1) * w.segment], want), "segment %d" % g
+    # every segment is a bijection of itself (holds at any size)
+    srt = np.sort(qh.reshape(w.batch, w.h_q, G, w.segment), axis=-1)
+    assert np.array_equal(srt, np.broadcast_to(np.arange(G * w.segment, dtype=np.int32).reshape(G, w.segment), srt.shape))
+    del qidx, qh, srt
+    # index remapping: kidx, Vt and the block means from the permutation stage, no K'; attention gathers from K
+    pr = make_problem(w, flags=w.flags | pbs.FLAG_INDEX_REMAP)
+    prk = make_problem(w, flags=w.flags | pbs.FLAG_INDEX_REMAP | pbs.FLAG_KBAR_IN_WS)
+    kidx, none, Vt = pbs.segment_permute(pr, torch.from_numpy(st["s_h"]).cuda(), st["K"], st["V"], ws=pipe.ws3)
+    assert none is None and np.array_equal(kidx.cpu().numpy(), st["kidx"])
+    pbs.block_mask(prk, st["Q"], st["K"], pipe.mask_bits, pipe.row_cnt, pipe.col_idx, pipe.ws3)
+    torch.cuda.synchronize()
+    assert np.array_equal(pipe.row_cnt.cpu().numpy(), st["row_cnt"])             # the means of K' came from the gather
+    rng = np.random.default_rng(6)
+    picks = [0, R - 1, R, T // 2, T - R, T - 1] + rng.integers(0, T, size=4).tolist()
+    rws = [[0, int(rng.integers(0, w.h_q)), int(i)] for i in picks]
+    Op, lse = pbs.attn_fwd(pr, st["Q"], st["K"], Vt, None, kidx, pipe.row_cnt, pipe.col_idx, pipe.Op, want_lse=True)
+    torch.cuda.synchronize()
+    want, want_lse = oracle.attn_rows(w.Q, st["Kp"], st["Vp"], None, st["kidx"], st["row_cnt"], st["col_idx"],
+                                      w.block, rws, want_lse=True)
+    for u, (b, h, i) in enumerate(rws):
+        sl = slice(i * w.block, (i + 1) * w.block)
+        check_close(to_host(Op[b, h, sl]), want[u], "bf16", "c3 row (%d,%d,%d), index remapping" % (b, h, i))
+        np.testing.assert_allclose(lse[b, h, sl].cpu().numpy(), want_lse[u], rtol=0, atol=2e-2)
+    assert torch.isfinite(Op).all()
+
+
 @pytest.mark.parametrize("rho", [0.05, 0.10, 0.25, 0.50, 1.0])
 def test_full_size_given_lists_on_sampled_rows(oracle, rho):
     """Config 5: identity key order, seeded block lists of density rho at N = 65536, attention only."""

@@ -113,6 +113,22 @@ def test_assignment_equals_cosine_brute_force_and_sigma_sorts_by_it(oracle_varia
         np.testing.assert_array_equal(qidx[0, h, G * segment:], np.arange(G * segment, N))   # the tail stays
 
 
+@pytest.mark.parametrize("N,block,segment,Hq,Hkv", [(96, 8, 32, 2, 1), (77, 4, 16, 4, 2)])
+def test_one_segment_at_a_time_equals_the_brute_force_order(oracle_variants, N, block, segment, Hq, Hkv):
+    # the per-segment entry (what the full-length GPU test can afford) against the numpy brute force, not against the
+    # whole-sequence entry: assignment by cosine argmax, then numpy's stable argsort
+    d = 8
+    Q, K = _rand(21, 1, Hq, N, d), _rand(22, 1, Hkv, N, d)
+    brute = _brute_assign(Q, K, block, segment)
+    for g in range(N // segment):
+        seg = np.arange(g * segment, (g + 1) * segment)
+        got = oracle_variants.query_permutation_segment(Q, K, block, segment, g)
+        for h in range(Hq):
+            np.testing.assert_array_equal(got[0, h], seg[np.argsort(brute[0, h, seg], kind="stable")])
+    with pytest.raises(RuntimeError):
+        oracle_variants.query_permutation_segment(Q, K, block, segment, N // segment)     # not a full segment
+
+
 def test_planted_clusters_are_recovered(oracle_variants):
     # keys: block j points along axis j (plus small noise); queries: positive multiples of a chosen axis.
     # Every query must be assigned to the block of its axis, unless that block lies in a later segment.
