@@ -59,7 +59,7 @@ class Workload:
 
     def describe(self):
         return dict(workload=self.name, batch=self.batch, h_q=self.h_q, h_kv=self.h_kv, n=self.n, d=self.d,
-                    block=self.block, segment=self.segment, tau=self.tau, storage=self.dtype)
+                    block=self.block, segment=self.segment, tau=float("%.6g" % self.tau), storage=self.dtype)
 
 
 def _rng(seed, stream):
@@ -116,6 +116,9 @@ def _plant(Q, K, seed, n_scatter, n_sink=4, bursts=0, burst_len=0):
 def _finish(name, Q, K, V, dtype, **kw):
     if dtype == "bf16":
         Q, K, V = round_to_bf16(Q), round_to_bf16(K), round_to_bf16(V)
+    # like the tensors, the threshold is rounded once to the type it is handed over in (a float in the C ABI), so
+    # that every consumer of the workload compares with the same number
+    kw["tau"] = float(np.float32(kw["tau"]))
     return Workload(name=name, batch=Q.shape[0], h_q=Q.shape[1], h_kv=K.shape[1], n=Q.shape[2], d=Q.shape[3],
                     dtype=dtype, Q=Q, K=K, V=V, **kw)
 

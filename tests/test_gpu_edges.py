@@ -307,7 +307,7 @@ def test_fp32_block_means_follow_the_row_order_of_the_definition(oracle, d, bloc
     # keep the pooled logits of the order of one: the means are dominated by the largest binades
     Q *= np.float32(2.0 ** -9)
     K *= np.float32(2.0 ** -9)
-    for tau in (0.5, 0.9, 0.99):
+    for tau in (0.5, float(np.float32(0.9)), float(np.float32(0.99))):   # as the float field of the problem holds them
         mask, row_cnt, col_idx = oracle.block_mask(Q, K, block, S, tau, flags=1)
         p = pbs.problem(1, Hq, Hkv, n, d, block, S, "f32", tau=tau, flags=1)
         bits, cnt, cols = pbs.block_mask(p, to_dev(Q, "f32"), to_dev(K, "f32"))
@@ -318,3 +318,19 @@ def test_fp32_block_means_follow_the_row_order_of_the_definition(oracle, d, bloc
         valid = np.arange(T)[None, None, None, :] < row_cnt[..., None]
         np.testing.assert_array_equal(np.where(valid, cols.cpu().numpy(), -1), col_idx)
         assert 0.2 < mask.mean() / 0.5 < 1.9               # a real selection, neither empty nor everything
+
+
+@pytest.mark.parametrize("h_q,n,segment", [(1, 65536, 64), (2, 65531, 128)])
+def test_block_mask_at_the_largest_block_count(oracle, h_q, n, segment):
+    # T = 4096 key blocks, the most the library accepts: a row of logits fills 32 KiB of LDS, so one query head takes
+    # two query blocks per workgroup and two heads one; near-uniform rows of thousands of columns; ragged last block
+    w = wl.planted("maxT", 11, h_q, 1, n, 64, 16, segment, 0.6, "bf16", 4)
+    assert w.T == 4096
+    mask, row_cnt, col_idx = oracle.block_mask(w.Q, w.K, w.block, w.segment, w.tau, flags=w.flags)
+    bits, cnt, cols = pbs.block_mask(make_problem(w), to_dev(w.Q, "bf16"), to_dev(w.K, "bf16"))
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(mask_from_bits(bits, w.T), mask)
+    np.testing.assert_array_equal(cnt.cpu().numpy(), row_cnt)
+    valid = np.arange(w.T)[None, None, None, :] < row_cnt[..., None]
+    np.testing.assert_array_equal(np.where(valid, cols.cpu().numpy(), -1), col_idx)
+
