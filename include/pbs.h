@@ -105,7 +105,7 @@ typedef struct {
     int32_t segment;  /* S of the paper */
     int32_t dtype;    /* pbs_dtype of Q, K, V, K', Vt, O', O */
     float tau;        /* mass threshold of Alg. 2, compared as (double)tau */
-    float scale;      /* logit scale; 0 means 1/sqrt(d) */
+    float scale;      /* logit scale; 0 means 1/sqrt(d) (formed in double where the arithmetic is fp64) */
     uint32_t flags;   /* PBS_FLAG_* */
 } pbs_problem;
 

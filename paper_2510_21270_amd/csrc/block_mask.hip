@@ -255,7 +255,7 @@ void select_kernel(const E *__restrict__ Qp,           // [bhq][n][d]
         for (int row = 0; row < RT; ++row)
 #pragma unroll
             for (int c = 0; c < CT; ++c)
-                if (j + c < ni_all) prob[row * Tpad + j + c] = __dmul_rn(acc[row][c], (double)g.scale);
+                if (j + c < ni_all) prob[row * Tpad + j + c] = __dmul_rn(acc[row][c], g.scale64);
     }
     __syncthreads();
 

@@ -375,7 +375,7 @@ __global__ __launch_bounds__(256) void scores_stats_f64_kernel(const E *__restri
     const int j1 = min(g.n, (chunk + 1) * keys_per_chunk);
     double m = -INFINITY, l = 0.0;
     for (int j = chunk * keys_per_chunk + threadIdx.x; j < j1; j += blockDim.x) {
-        const double v = dot_f64(q, Kh + (size_t)j * g.d, g.d) * (double)g.scale;
+        const double v = dot_f64(q, Kh + (size_t)j * g.d, g.d) * g.scale64;
         const double mn = fmax(m, v);
         l = l * exp(m - mn) + exp(v - mn);
         m = mn;
@@ -429,7 +429,7 @@ __global__ __launch_bounds__(256) void scores_final_f64_kernel(const E *__restri
         if ((int)threadIdx.x < nr) st[threadIdx.x] = stats[(size_t)bh * bl + r0 + threadIdx.x];
         __syncthreads();
         for (int rr = 0; rr < nr; ++rr) {
-            const double v = dot_f64(q[rr], krow, g.d) * (double)g.scale;
+            const double v = dot_f64(q[rr], krow, g.d) * g.scale64;
             acc += exp(v - st[rr].x) / st[rr].y;
         }
     }

@@ -26,6 +26,8 @@ struct Geo {
     int R;      // blocks per segment
     int G;      // full segments
     float scale;
+    double scale64; // the scale in the fp64 arithmetic that decides masks and fp32-input scores: the caller's float, or
+                    // 1/sqrt(d) formed in double when the caller leaves the default (the two differ in the 8th digit)
     double tau;
     unsigned flags;
 };

@@ -43,6 +43,7 @@ inline Geo make_geo(const pbs_problem *p)
     g.R = p->segment / p->block;
     g.G = p->n / p->segment;
     g.scale = p->scale > 0.0f ? p->scale : (float)(1.0 / sqrt((double)p->d));
+    g.scale64 = p->scale > 0.0f ? (double)p->scale : 1.0 / sqrt((double)p->d);
     g.tau = (double)p->tau;
     g.flags = p->flags;
     return g;

@@ -366,7 +366,7 @@ def test_random_shapes_stage_by_stage(lib, oracle, seed, wide):
     w = _random_shape(seed, wide)
     sigma = seed % 3 == 0
     qidx = wl.random_segment_perm(seed, w.batch * w.h_q, w.n, w.segment).reshape(w.batch, w.h_q, w.n) if sigma else None
-    scale = [0.0, 0.05, 0.2][seed % 3]                  # 0 = the default 1 / sqrt(d)
+    scale = [0.0, float(np.float32(0.05)), float(np.float32(0.2))][seed % 3]   # 0 = the default 1 / sqrt(d); else a float
     res = oracle.pipeline(w.Q, w.K, w.V, w.block, w.segment, w.tau, scale=scale, flags=w.flags, qidx=qidx)
     p = make_problem(w, scale=scale)
     what = "%s batch=%d n=%d hq=%d hkv=%d d=%d block=%d segment=%d tau=%g flags=%d sigma=%s scale=%g" % (
