@@ -21,6 +21,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0       # MI355X dense bf16 matrix peak
+FP32_VECTOR_PEAK_TFLOPS = 157.3       # published fp32 vector rate (the shapes outside the matrix-core path)
 HBM_PEAK_GBS = 8000.0                # MI355X HBM3E
 
 
@@ -387,6 +388,11 @@ def main():
                 "frac_from_visited_blocks": visited_tflops / MFMA_BF16_PEAK_TFLOPS,
                 "traffic": traffic, "traffic_source": traffic_src or "not measured for this workload",
                 "avg_launch_ms": stage_ms["attn_fwd"]}
+    if not (w.dtype == "bf16" and w.d == 128 and w.block in (64, 128)):
+        # every other shape runs on fp32 vector arithmetic (attn_vector_kernel): rated against the chip's fp32 vector
+        # peak (256 compute units x 128 FMA lanes x 2 x 2.4 GHz = 157.3 TFLOP/s)
+        roofline.update(bound="alu", peak=FP32_VECTOR_PEAK_TFLOPS, frac=attn_tflops / FP32_VECTOR_PEAK_TFLOPS,
+                        frac_from_visited_blocks=visited_tflops / FP32_VECTOR_PEAK_TFLOPS)
     if given:
         # Caller-supplied lists drawn independently per query head: no two heads of a group share K'/V'^T tiles, so
         # every listed block fetches its 2 * block * d tile bytes (128 FLOP per byte), plus Q' and O' once.  Whichever
@@ -420,7 +426,7 @@ def main():
         "context": {"paper_h100_128k_ms": {"flashattention": 443.29, "pbs_total": 159.87, "speedup": 2.77},
                     "input_generation_s": t_gen, **extras},
     }
-    if "mfma_alone_tflops" in extras:
+    if "mfma_alone_tflops" in extras and out["roofline"]["bound"] != "alu":
         out["roofline"]["frac_of_mfma_alone_random_operands"] = attn_tflops / extras["mfma_alone_tflops"]["random_operands"]
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, visited=None if given else visited)
